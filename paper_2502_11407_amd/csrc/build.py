@@ -1,0 +1,100 @@
+"""Build libgensor.so for gfx950: one translation unit per group of kernel instances
+(generated from lattice.py), the registry table, the constructor and the C ABI."""
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+PKG = os.path.dirname(HERE)
+GEN = os.path.join(HERE, "_build")
+LIB = os.path.join(PKG, "libgensor.so")
+sys.path.insert(0, HERE)
+import lattice  # noqa: E402
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", HERE,
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wno-unused-command-line-argument"]
+PER_TU = 4
+
+
+def _write_if_changed(path, text):
+    if os.path.exists(path) and open(path).read() == text:
+        return
+    with open(path, "w") as f:
+        f.write(text)
+
+
+def generate():
+    os.makedirs(GEN, exist_ok=True)
+    L = lattice.lattice()
+    tus = []
+    for t in range(0, len(L), PER_TU):
+        group = L[t:t + PER_TU]
+        src = ['#include "registry.hpp"', "namespace gensor {"]
+        for d in group:
+            src.append("typedef %s C_%d;" % (lattice.cfg_type(d), d["id"]))
+            src.append("hipError_t launch_%d(const KernelArgs& a, hipStream_t st) { return launch_instance<C_%d>(a, st); }"
+                       % (d["id"], d["id"]))
+        src.append("}  // namespace gensor\n")
+        path = os.path.join(GEN, "inst_%03d.hip" % (t // PER_TU))
+        _write_if_changed(path, "\n".join(src))
+        tus.append(path)
+    reg = ['#include "registry.hpp"', "#if !defined(__HIP_DEVICE_COMPILE__)", "namespace gensor {"]
+    for d in L:
+        reg.append("hipError_t launch_%d(const KernelArgs&, hipStream_t);" % d["id"])
+    reg.append("const InstanceDesc g_instances[] = {")
+    for d in L:
+        es = 4 if d["dt"] == "f32" else 2
+        kg = (64 // d["mb"]) * (16 // es)
+        a_bytes = d["bm"] * d["bk"] * es
+        b_bytes = d["bn"] * d["bk"] * es if d["bsrc"] == "KC" else d["bk"] * (d["bn"] * es + 32)
+        lds = (a_bytes + b_bytes) * d["stages"]
+        threads = (d["bm"] // d["wm"]) * (d["bn"] // d["wn"]) * 64
+        reg.append("  {%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, launch_%d}," % (
+            d["id"], lattice.DT[d["dt"]], lattice.DT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"],
+            d["vm"], d["vn"], lattice.BSRC[d["bsrc"]], d["vec"], d["stages"], d["direct"], lds, threads, kg, d["id"]))
+    reg.append("};")
+    reg.append("const int g_num_instances = %d;" % len(L))
+    reg.append("}  // namespace gensor")
+    reg.append("#endif\n")
+    path = os.path.join(GEN, "registry.hip")
+    _write_if_changed(path, "\n".join(reg))
+    tus.append(path)
+    return tus
+
+
+def _compile(src):
+    obj = os.path.join(GEN, os.path.basename(src).rsplit(".", 1)[0] + ".o")
+    deps = [src, os.path.join(HERE, "gemm_kernel.hpp"), os.path.join(HERE, "registry.hpp"),
+            os.path.join(HERE, "host_common.hpp"), os.path.join(PKG, "..", "include", "gensor.h")]
+    if os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps if os.path.exists(d)):
+        return obj
+    cmd = [HIPCC] + FLAGS + ["-x", "hip", "-c", src, "-o", obj]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on %s:\n%s" % (src, err))
+    if err.strip():
+        sys.stderr.write(err + "\n")
+    return obj
+
+
+def build(force=False, jobs=None):
+    tus = generate()
+    tus += [os.path.join(HERE, "gensor_api.cpp"), os.path.join(HERE, "constructor.cpp")]
+    if force:
+        for f in os.listdir(GEN):
+            if f.endswith(".o"):
+                os.remove(os.path.join(GEN, f))
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(_compile, tus))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force="--force" in sys.argv))

@@ -1,0 +1,501 @@
+// Scheduled dense-contraction kernel for gfx950 (CDNA4): one template covers GEMM, batched
+// matmul and implicit-GEMM convolution.  Every template parameter is a schedule primitive
+// of the construction graph (Section IV-A of the paper: per-level tiles, caching, virtual
+// threads; Table I: unroll, vectorise):
+//
+//   BM,BN,BK   T_2  workgroup tile, staged in LDS                ("cache" primitive)
+//   WM,WN      T_1  wavefront tile, fp32 accumulators in registers
+//   MB         MFMA block edge (32: 32x32 blocks, 16: 16x16 blocks); fixes the MFMA k depth
+//   VM,VN      virtual-thread split: the wave tile is V strided pieces of T_0 = T_1/V rows
+//   STAGES     LDS buffers (1: single buffer, 2: double buffer)
+//   VEC        global accesses are 16-byte vectors (true) or single elements (false)
+//   DIRECT     K-contiguous operands go global->LDS without passing through registers
+//
+// Operand sources.  A (the m x k operand) is always k-contiguous: A[m][k].  B is
+//   KC   k-contiguous,  B stored [n][k]   (column-major B / "transB")
+//   NC   n-contiguous,  B stored [k][n]   (row-major B)
+//   CONV n = (image, out row, out col), k = (channel, filter row, filter col): element
+//        (k, n) is gathered from the NCHW input, zero outside the image; m = filter.
+//
+// LDS layouts.  k-contiguous tiles are [rows][BK] in 16-byte chunks; chunk c of row r sits
+// at chunk c ^ ((r / rows_per_256B) % chunks_per_row), which makes a wave's b128 fragment
+// reads hit 64 distinct banks per 16 lanes.  n-contiguous tiles are [BK][BN + pad].
+//
+// MFMA operand convention (per lane l of a 64-wide wave):
+//   32x32 blocks: row/col = l % 32, holds the 16-byte chunk  2*kstep + l/32  of that row
+//   16x16 blocks: row/col = l % 16, holds the 16-byte chunk  4*kstep + l/16  of that row
+// For 16-bit types a chunk is 8 consecutive k and feeds one MFMA; for fp32 a chunk is 4
+// consecutive k and feeds 4 MFMAs (element t of the chunk at step t).  The order in which k
+// is consumed differs from memory order, identically for both operands.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gensor {
+
+enum BSrc { B_KC = 0, B_NC = 1, B_CONV = 2 };
+
+struct KernelArgs {
+  const void* A;
+  const void* B;
+  void* C;
+  int32_t M, N, K;                 // GEMM-view extents
+  int64_t lda, ldb, ldc;           // elements
+  int64_t strideA, strideB, strideC;
+  float alpha, beta;
+  int32_t tiles_m, tiles_n, batch;
+  int32_t panel;                   // tile rows per panel in the workgroup->tile map
+  // convolution geometry (B_CONV only)
+  int32_t cC, cH, cW, cR, cS, cP, cQ, cStride, cPad;
+};
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+#define GENSOR_LDS __attribute__((address_space(3)))
+
+struct f16_t { typedef _Float16 native; };
+struct bf16_t { typedef __bf16 native; };
+struct f32_t { typedef float native; };
+
+template <typename T> struct ElemSize { static constexpr int value = 2; };
+template <> struct ElemSize<f32_t> { static constexpr int value = 4; };
+
+// ---------------------------------------------------------------- scalar conversions
+template <typename T> __device__ inline float to_float(const void* p, int64_t i);
+template <> __device__ inline float to_float<f32_t>(const void* p, int64_t i) { return ((const float*)p)[i]; }
+template <> __device__ inline float to_float<f16_t>(const void* p, int64_t i) { return (float)((const _Float16*)p)[i]; }
+template <> __device__ inline float to_float<bf16_t>(const void* p, int64_t i) {
+  return __builtin_bit_cast(float, ((uint32_t)((const uint16_t*)p)[i]) << 16);
+}
+template <typename T> __device__ inline void store_out(void* p, int64_t i, float v);
+template <> __device__ inline void store_out<f32_t>(void* p, int64_t i, float v) { ((float*)p)[i] = v; }
+template <> __device__ inline void store_out<f16_t>(void* p, int64_t i, float v) { ((_Float16*)p)[i] = (_Float16)v; }
+template <> __device__ inline void store_out<bf16_t>(void* p, int64_t i, float v) {
+  uint32_t u = __builtin_bit_cast(uint32_t, v);                 // round to nearest even
+  uint32_t r = (u & 0x7fffffffu) > 0x7f800000u ? 0x7fc0u : ((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+  ((uint16_t*)p)[i] = (uint16_t)r;
+}
+
+// ---------------------------------------------------------------- MFMA wrappers
+// (the bits travel through a by-value argument: a bit cast applied directly to a vector
+// element expression reads element 0 whatever the index)
+__device__ inline float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+template <typename T, int MB> struct Mfma;
+template <> struct Mfma<f16_t, 32> {
+  typedef f32x16 Acc;
+  static constexpr int NACC = 16;
+  __device__ static inline void run(const u32x4& a, const u32x4& b, Acc& c) {
+    c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Mfma<f16_t, 16> {
+  typedef f32x4 Acc;
+  static constexpr int NACC = 4;
+  __device__ static inline void run(const u32x4& a, const u32x4& b, Acc& c) {
+    c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Mfma<bf16_t, 32> {
+  typedef f32x16 Acc;
+  static constexpr int NACC = 16;
+  __device__ static inline void run(const u32x4& a, const u32x4& b, Acc& c) {
+    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Mfma<bf16_t, 16> {
+  typedef f32x4 Acc;
+  static constexpr int NACC = 4;
+  __device__ static inline void run(const u32x4& a, const u32x4& b, Acc& c) {
+    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Mfma<f32_t, 32> {   // true fp32 multiply-add: 32x32x2 per step, 4 steps per chunk
+  typedef f32x16 Acc;
+  static constexpr int NACC = 16;
+  __device__ static inline void run(const u32x4& a, const u32x4& b, Acc& c) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      c = __builtin_amdgcn_mfma_f32_32x32x2f32(as_f32(a[t]), as_f32(b[t]), c, 0, 0, 0);
+  }
+};
+template <> struct Mfma<f32_t, 16> {   // 16x16x4 per step
+  typedef f32x4 Acc;
+  static constexpr int NACC = 4;
+  __device__ static inline void run(const u32x4& a, const u32x4& b, Acc& c) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      c = __builtin_amdgcn_mfma_f32_16x16x4f32(as_f32(a[t]), as_f32(b[t]), c, 0, 0, 0);
+  }
+};
+
+// ---------------------------------------------------------------- schedule -> constants
+template <typename T_, typename OutT_, int BM_, int BN_, int BK_, int WM_, int WN_, int MB_, int VM_, int VN_,
+          int BSRC_, bool VEC_, int STAGES_, bool DIRECT_>
+struct Cfg {
+  typedef T_ T;
+  typedef OutT_ OutT;
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MB = MB_, VM = VM_, VN = VN_;
+  static constexpr int BSRC = BSRC_, STAGES = STAGES_;
+  static constexpr bool VEC = VEC_, DIRECT = DIRECT_;
+  static constexpr int ES = ElemSize<T>::value;
+  static constexpr int EPC = 16 / ES;                        // elements per 16-byte chunk
+  static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, WAVES = WAVES_M * WAVES_N;
+  static constexpr int THREADS = WAVES * 64;
+  static constexpr int MBLK = WM / MB, NBLK = WN / MB;       // MFMA blocks per wave tile
+  static constexpr int LANE_GROUPS = 64 / MB;                // 2 (32x32) or 4 (16x16)
+  static constexpr int KG = LANE_GROUPS * EPC;               // k consumed per fragment read
+  static constexpr int KSTEPS = BK / KG;                     // the "unroll" of the schedule
+  // k-contiguous LDS tile: [rows][BK], 16-byte chunks, xor swizzle
+  static constexpr int PITCH_K = BK * ES;                    // bytes per row
+  static constexpr int CPR = PITCH_K / 16;                   // chunks per row
+  static constexpr int RPP = (PITCH_K >= 256) ? 1 : 256 / PITCH_K;   // rows per 256-byte bank period
+  // n-contiguous LDS tile: [BK][BN] + pad
+  static constexpr int PITCH_N = BN * ES + 32;
+  static constexpr int A_BYTES = BM * PITCH_K;
+  static constexpr int B_BYTES = (BSRC == B_KC) ? BN * PITCH_K : BK * PITCH_N;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = STAGE_BYTES * STAGES;
+  static constexpr int A_CHUNKS = BM * CPR;
+  static constexpr int B_CHUNKS = (BSRC == B_KC) ? BN * CPR : BK * (BN * ES / 16);
+  static constexpr int A_LOADS = (A_CHUNKS + THREADS - 1) / THREADS;
+  static constexpr int B_LOADS = (B_CHUNKS + THREADS - 1) / THREADS;
+  static_assert(BM % WM == 0 && BN % WN == 0, "wave tile must divide workgroup tile");
+  static_assert(WM % (MB * VM) == 0 && WN % (MB * VN) == 0, "virtual pieces must be whole MFMA blocks");
+  static_assert(BK % KG == 0, "BK must be a multiple of the fragment k extent");
+  static_assert(MB == 32 || MB == 16, "MFMA block edge");
+  static_assert(WAVES >= 1 && WAVES <= 16, "waves per workgroup");
+  static_assert(!DIRECT || (VEC && BSRC == B_KC), "direct-to-LDS needs vector loads of k-contiguous operands");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS capacity");
+};
+
+__device__ inline int swizzled_chunk(int row, int chunk, int rpp, int cpr) { return chunk ^ ((row / rpp) % cpr); }
+
+// ---------------------------------------------------------------- the kernel
+template <typename C>
+__global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArgs args) {
+  typedef typename C::T T;
+  typedef Mfma<T, C::MB> MF;
+  typedef typename MF::Acc Acc;
+  constexpr int ES = C::ES, EPC = C::EPC, BM = C::BM, BN = C::BN, BK = C::BK, MB = C::MB;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  GENSOR_LDS char* lds = (GENSOR_LDS char*)smem;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wave_m = wave / C::WAVES_N;
+  const int wave_n = wave % C::WAVES_N;
+
+  // ---- workgroup -> (batch, tile_m, tile_n).  Consecutive workgroup ids are dealt
+  // round-robin to the 8 XCDs; give each XCD a contiguous range of tiles, and walk tiles
+  // in panels of `panel` tile rows so that the tiles resident on one XCD share operand
+  // slabs in that XCD's L2.
+  const int tiles_per_batch = args.tiles_m * args.tiles_n;
+  const int total = tiles_per_batch * args.batch;
+  int wg = blockIdx.x;
+  if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
+  const int bidx = wg / tiles_per_batch;
+  int t = wg - bidx * tiles_per_batch;
+  int tile_m, tile_n;
+  {
+    const int panel = args.panel;
+    const int per_panel = panel * args.tiles_n;
+    const int pi = t / per_panel;
+    const int rows_here = min(panel, args.tiles_m - pi * panel);
+    const int r = t - pi * per_panel;
+    tile_m = pi * panel + r % rows_here;
+    tile_n = r / rows_here;
+  }
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * BN;
+
+  const char* Ab = (const char*)args.A + (int64_t)bidx * args.strideA * ES;
+  const char* Bb = (const char*)args.B + (int64_t)bidx * args.strideB * ES;
+
+  // ---- accumulators
+  Acc acc[C::MBLK][C::NBLK];
+#pragma unroll
+  for (int i = 0; i < C::MBLK; ++i)
+#pragma unroll
+    for (int j = 0; j < C::NBLK; ++j)
+#pragma unroll
+      for (int v = 0; v < MF::NACC; ++v) acc[i][j][v] = 0.f;
+
+  // ---- staging registers (global -> registers -> LDS)
+  u32x4 ra[C::DIRECT ? 1 : C::A_LOADS];
+  u32x4 rb[C::DIRECT ? 1 : C::B_LOADS];
+
+  // element (row, k) of A / element (k, col) of B as float-convertible scalars, for the scalar path
+  auto a_elem_bits = [&](int row, int k) -> uint32_t {
+    if (row < args.M && k < args.K) {
+      int64_t idx = (int64_t)row * args.lda + k;
+      if constexpr (ES == 4) return ((const uint32_t*)Ab)[idx];
+      else return ((const uint16_t*)Ab)[idx];
+    }
+    return 0u;
+  };
+  auto b_elem_bits = [&](int k, int col) -> uint32_t {
+    if (col >= args.N || k >= args.K) return 0u;
+    int64_t idx;
+    if constexpr (C::BSRC == B_KC) idx = (int64_t)col * args.ldb + k;
+    else if constexpr (C::BSRC == B_NC) idx = (int64_t)k * args.ldb + col;
+    else {
+      const int rs = args.cR * args.cS;
+      const int c = k / rs, rr = (k - c * rs) / args.cS, ss = k - c * rs - rr * args.cS;
+      const int pq = args.cP * args.cQ;
+      const int img = col / pq, p = (col - img * pq) / args.cQ, q = col - img * pq - p * args.cQ;
+      const int y = p * args.cStride - args.cPad + rr, x = q * args.cStride - args.cPad + ss;
+      if (y < 0 || y >= args.cH || x < 0 || x >= args.cW) return 0u;
+      idx = (((int64_t)img * args.cC + c) * args.cH + y) * args.cW + x;
+    }
+    if constexpr (ES == 4) return ((const uint32_t*)Bb)[idx];
+    else return ((const uint16_t*)Bb)[idx];
+  };
+  auto pack_chunk = [&](auto&& elem) -> u32x4 {   // elem(e) for e in [0, EPC)
+    u32x4 v;
+    if constexpr (ES == 4) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = elem(e);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = elem(2 * e) | (elem(2 * e + 1) << 16);
+    }
+    return v;
+  };
+
+  // ---- global -> registers for the k-tile starting at k0
+  auto load_a = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < C::A_LOADS; ++i) {
+      const int q = tid + i * C::THREADS;
+      if (C::A_CHUNKS % C::THREADS != 0 && q >= C::A_CHUNKS) break;
+      const int row = q / C::CPR, ch = q % C::CPR;
+      const int gm = m0 + row, gk = k0 + ch * EPC;
+      if constexpr (C::VEC) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (gm < args.M && gk < args.K) v = *(const u32x4*)(Ab + ((int64_t)gm * args.lda + gk) * ES);
+        ra[i] = v;
+      } else {
+        ra[i] = pack_chunk([&](int e) { return a_elem_bits(gm, gk + e); });
+      }
+    }
+  };
+  auto load_b = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < C::B_LOADS; ++i) {
+      const int q = tid + i * C::THREADS;
+      if (C::B_CHUNKS % C::THREADS != 0 && q >= C::B_CHUNKS) break;
+      if constexpr (C::BSRC == B_KC) {
+        const int row = q / C::CPR, ch = q % C::CPR;
+        const int gn = n0 + row, gk = k0 + ch * EPC;
+        if constexpr (C::VEC) {
+          u32x4 v = {0u, 0u, 0u, 0u};
+          if (gn < args.N && gk < args.K) v = *(const u32x4*)(Bb + ((int64_t)gn * args.ldb + gk) * ES);
+          rb[i] = v;
+        } else {
+          rb[i] = pack_chunk([&](int e) { return b_elem_bits(gk + e, gn); });
+        }
+      } else {
+        constexpr int CPRN = BN * ES / 16;
+        const int krow = q / CPRN, ch = q % CPRN;
+        const int gk = k0 + krow, gn = n0 + ch * EPC;
+        if constexpr (C::VEC && C::BSRC == B_NC) {
+          u32x4 v = {0u, 0u, 0u, 0u};
+          if (gk < args.K && gn < args.N) v = *(const u32x4*)(Bb + ((int64_t)gk * args.ldb + gn) * ES);
+          rb[i] = v;
+        } else {
+          rb[i] = pack_chunk([&](int e) { return b_elem_bits(gk, gn + e); });
+        }
+      }
+    }
+  };
+  // ---- registers -> LDS stage `st`
+  auto store_a = [&](int st) {
+    GENSOR_LDS char* base = lds + st * C::STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < C::A_LOADS; ++i) {
+      const int q = tid + i * C::THREADS;
+      if (C::A_CHUNKS % C::THREADS != 0 && q >= C::A_CHUNKS) break;
+      const int row = q / C::CPR, ch = q % C::CPR;
+      *(GENSOR_LDS u32x4*)(base + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16) = ra[i];
+    }
+  };
+  auto store_b = [&](int st) {
+    GENSOR_LDS char* base = lds + st * C::STAGE_BYTES + C::A_BYTES;
+#pragma unroll
+    for (int i = 0; i < C::B_LOADS; ++i) {
+      const int q = tid + i * C::THREADS;
+      if (C::B_CHUNKS % C::THREADS != 0 && q >= C::B_CHUNKS) break;
+      if constexpr (C::BSRC == B_KC) {
+        const int row = q / C::CPR, ch = q % C::CPR;
+        *(GENSOR_LDS u32x4*)(base + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16) = rb[i];
+      } else {
+        constexpr int CPRN = BN * ES / 16;
+        const int krow = q / CPRN, ch = q % CPRN;
+        *(GENSOR_LDS u32x4*)(base + krow * C::PITCH_N + ch * 16) = rb[i];
+      }
+    }
+  };
+  // ---- global -> LDS directly (k-contiguous operands, vector path).  Each wave-level
+  // load deposits lane l's 16 bytes at (instruction base) + 16*l, so the swizzle is applied
+  // to the global address: the lane that owns LDS chunk slot (row, pc) fetches logical
+  // chunk pc ^ f(row).  Chunks outside the matrix are fetched from a clamped in-range
+  // address and the row/column they belong to is never stored, or contributes to k >= K
+  // only if K is not a multiple of BK, which the host rules out for this mode.
+  auto direct_tile = [&](const char* gbase, int64_t ld, int row0, int nrows_total, int k0, GENSOR_LDS char* dst, int chunks) {
+    for (int q0 = wave * 64; q0 < chunks; q0 += C::THREADS) {
+      const int q = q0 + lane;
+      const int row = q / C::CPR, pc = q % C::CPR;
+      const int ch = swizzled_chunk(row, pc, C::RPP, C::CPR);
+      int gr = row0 + row;
+      gr = gr < nrows_total ? gr : nrows_total - 1;
+      const char* src = gbase + ((int64_t)gr * ld + k0 + ch * EPC) * ES;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (GENSOR_LDS void*)(dst + q0 * 16), 16, 0, 0);
+    }
+  };
+  auto direct_load = [&](int k0, int st) {
+    GENSOR_LDS char* base = lds + st * C::STAGE_BYTES;
+    direct_tile(Ab, args.lda, m0, args.M, k0, base, C::A_CHUNKS);
+    direct_tile(Bb, args.ldb, n0, args.N, k0, base + C::A_BYTES, C::B_CHUNKS);
+  };
+
+  // ---- fragment reads + MFMA for one LDS stage
+  const int frow = lane % MB;          // row / column inside an MFMA block
+  const int fgrp = lane / MB;          // which chunk of the k group this lane holds
+  auto block_row = [&](int bi) {       // first row of MFMA block bi of this wave inside the BM tile
+    constexpr int PER = C::MBLK / C::VM;
+    return (bi / PER) * (BM / C::VM) + wave_m * (C::WM / C::VM) + (bi % PER) * MB;
+  };
+  auto block_col = [&](int bj) {
+    constexpr int PER = C::NBLK / C::VN;
+    return (bj / PER) * (BN / C::VN) + wave_n * (C::WN / C::VN) + (bj % PER) * MB;
+  };
+  auto compute = [&](int st) {
+    GENSOR_LDS char* abase = lds + st * C::STAGE_BYTES;
+    GENSOR_LDS char* bbase = abase + C::A_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < C::KSTEPS; ++ks) {
+      u32x4 af[C::MBLK], bf[C::NBLK];
+      const int ch = ks * C::LANE_GROUPS + fgrp;
+#pragma unroll
+      for (int bi = 0; bi < C::MBLK; ++bi) {
+        const int row = block_row(bi) + frow;
+        af[bi] = *(GENSOR_LDS u32x4*)(abase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16);
+      }
+#pragma unroll
+      for (int bj = 0; bj < C::NBLK; ++bj) {
+        if constexpr (C::BSRC == B_KC) {
+          const int row = block_col(bj) + frow;
+          bf[bj] = *(GENSOR_LDS u32x4*)(bbase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16);
+        } else if constexpr (ES == 4) {
+          // fp32, [k][n] tile: element t of this lane's chunk is k = ks*KG + fgrp*4 + t
+          const int col = block_col(bj) + frow;
+          u32x4 v;
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt)
+            v[tt] = *(GENSOR_LDS uint32_t*)(bbase + (ks * C::KG + fgrp * 4 + tt) * C::PITCH_N + col * 4);
+          bf[bj] = v;
+        } else {
+          // 16-bit, [k][n] tile: two transposing reads.  In each 16-lane group, lane s
+          // fetches 4 consecutive n of row (s/4) and receives, for column s, the 4
+          // consecutive k of the group's rows.
+          const int g = lane >> 4, s = lane & 15;
+          int krow, col;
+          if constexpr (MB == 32) {    // groups: (g%2) picks the 16-column half, (g/2) the 8-deep k half
+            krow = ks * C::KG + (g >> 1) * 8 + (s >> 2);
+            col = block_col(bj) + (g & 1) * 16 + (s & 3) * 4;
+          } else {                     // 16x16 blocks: group g holds k = 8g..8g+7
+            krow = ks * C::KG + g * 8 + (s >> 2);
+            col = block_col(bj) + (s & 3) * 4;
+          }
+          GENSOR_LDS char* p = bbase + krow * C::PITCH_N + col * 2;
+          s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)p);
+          s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + 4 * C::PITCH_N));
+          u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+          u32x4 v = {l2[0], l2[1], h2[0], h2[1]};
+          bf[bj] = v;
+        }
+      }
+#pragma unroll
+      for (int bi = 0; bi < C::MBLK; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < C::NBLK; ++bj) MF::run(af[bi], bf[bj], acc[bi][bj]);
+    }
+  };
+
+  // ---- main loop over k tiles
+  const int nk = (args.K + BK - 1) / BK;
+  if constexpr (C::DIRECT) {
+    direct_load(0, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's deposits have landed
+      __syncthreads();                           // everyone's deposits visible; previous compute finished
+      if (kt + 1 < nk) direct_load((kt + 1) * BK, (kt + 1) % C::STAGES);
+      compute(kt % C::STAGES);
+      if constexpr (C::STAGES == 1) __syncthreads();
+    }
+  } else {
+    load_a(0);
+    load_b(0);
+    store_a(0);
+    store_b(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      const bool more = kt + 1 < nk;
+      if (more) {
+        load_a((kt + 1) * BK);
+        load_b((kt + 1) * BK);
+      }
+      compute(kt % C::STAGES);
+      if constexpr (C::STAGES == 1) __syncthreads();
+      if (more) {
+        store_a((kt + 1) % C::STAGES);
+        store_b((kt + 1) % C::STAGES);
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- epilogue: C = alpha * acc + beta * C.  In a 32x32 block lane l holds column l%32
+  // of rows 8*(v/4) + 4*(l/32) + v%4; in a 16x16 block column l%16 of rows 4*(l/16) + v.
+  typedef typename C::OutT OutT;
+  char* Cb = (char*)args.C + (int64_t)bidx * args.strideC * ElemSize<OutT>::value;
+  const float alpha = args.alpha, beta = args.beta;
+#pragma unroll
+  for (int bi = 0; bi < C::MBLK; ++bi)
+#pragma unroll
+    for (int bj = 0; bj < C::NBLK; ++bj) {
+      const int col = n0 + block_col(bj) + frow;
+#pragma unroll
+      for (int v = 0; v < MF::NACC; ++v) {
+        int r;
+        if constexpr (MB == 32) r = 8 * (v / 4) + 4 * fgrp + (v % 4);
+        else r = 4 * fgrp + v;
+        const int row = m0 + block_row(bi) + r;
+        if (row < args.M && col < args.N) {
+          int64_t idx;
+          if constexpr (C::BSRC == B_CONV) {
+            // output O[img][filter][p][q]: row = filter, col = (img, p, q)
+            const int pq = args.cP * args.cQ;
+            const int img = col / pq;
+            idx = ((int64_t)img * args.M + row) * pq + (col - img * pq);
+          } else {
+            idx = (int64_t)row * args.ldc + col;
+          }
+          float val = alpha * acc[bi][bj][v];
+          if (beta != 0.f) val += beta * to_float<OutT>(Cb, idx);
+          store_out<OutT>(Cb, idx, val);
+        }
+      }
+    }
+}
+
+}  // namespace gensor

@@ -1,0 +1,230 @@
+// C ABI of the operators: argument validation, GEMM view of each operator, lookup of the
+// kernel instance a schedule names, and the launch.  No device memory is allocated here.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <tuple>
+
+#include "../../include/gensor.h"
+#include "host_common.hpp"
+#include "registry.hpp"
+
+using namespace gensor;
+
+extern "C" const char* gensor_status_string(gensor_status st) {
+  switch (st) {
+    case GENSOR_OK: return "ok";
+    case GENSOR_ERR_INVALID_ARG: return "invalid argument";
+    case GENSOR_ERR_UNSUPPORTED: return "unsupported combination";
+    case GENSOR_ERR_NO_SCHEDULE: return "no feasible schedule / schedule does not match a compiled instance";
+    case GENSOR_ERR_WORKSPACE: return "workspace too small";
+    case GENSOR_ERR_DEVICE: return "HIP launch error";
+  }
+  return "unknown status";
+}
+
+extern "C" int32_t gensor_num_instances(void) { return g_num_instances; }
+
+namespace gensor {
+
+static bool valid_dtype(int d) { return d == GENSOR_F32 || d == GENSOR_F16 || d == GENSOR_BF16; }
+
+gensor_status gemm_view(const gensor_problem* p, GemmView* v) {
+  if (!p || !v) return GENSOR_ERR_INVALID_ARG;
+  if (!valid_dtype(p->in_dtype) || !valid_dtype(p->out_dtype)) return GENSOR_ERR_INVALID_ARG;
+  if (p->out_dtype != GENSOR_F32 && p->out_dtype != p->in_dtype) return GENSOR_ERR_UNSUPPORTED;
+  std::memset(v, 0, sizeof(*v));
+  v->in_dtype = p->in_dtype;
+  v->out_dtype = p->out_dtype;
+  v->esize = p->in_dtype == GENSOR_F32 ? 4 : 2;
+  v->osize = p->out_dtype == GENSOR_F32 ? 4 : 2;
+  if (p->op == GENSOR_OP_GEMM || p->op == GENSOR_OP_BMM) {
+    if (p->M <= 0 || p->N <= 0 || p->K <= 0) return GENSOR_ERR_INVALID_ARG;
+    if (p->op == GENSOR_OP_BMM && p->batch <= 0) return GENSOR_ERR_INVALID_ARG;
+    if ((p->transA != 0 && p->transA != 1) || (p->transB != 0 && p->transB != 1)) return GENSOR_ERR_INVALID_ARG;
+    if (p->transA) return GENSOR_ERR_UNSUPPORTED;     // A must be k-contiguous
+    v->M = p->M; v->N = p->N; v->K = p->K;
+    v->batch = p->op == GENSOR_OP_BMM ? p->batch : 1;
+    v->bsrc = p->transB ? B_KC : B_NC;
+  } else if (p->op == GENSOR_OP_CONV2D) {
+    if (p->n <= 0 || p->c <= 0 || p->h <= 0 || p->w <= 0 || p->k <= 0 || p->r <= 0 || p->s <= 0) return GENSOR_ERR_INVALID_ARG;
+    if (p->stride <= 0 || p->pad < 0) return GENSOR_ERR_INVALID_ARG;
+    if (p->h + 2 * p->pad < p->r || p->w + 2 * p->pad < p->s) return GENSOR_ERR_INVALID_ARG;
+    v->P = (p->h + 2 * p->pad - p->r) / p->stride + 1;
+    v->Q = (p->w + 2 * p->pad - p->s) / p->stride + 1;
+    v->M = p->k;
+    v->N = p->n * v->P * v->Q;
+    v->K = p->c * p->r * p->s;
+    v->batch = 1;
+    v->bsrc = B_CONV;
+  } else {
+    return GENSOR_ERR_INVALID_ARG;
+  }
+  if (v->M > INT32_MAX || v->N > INT32_MAX || v->K > INT32_MAX || v->batch > INT32_MAX) return GENSOR_ERR_UNSUPPORTED;
+  return GENSOR_OK;
+}
+
+void schedule_from_instance(const InstanceDesc& d, gensor_schedule* s) {
+  std::memset(s, 0, sizeof(*s));
+  s->version = GENSOR_SCHEDULE_VERSION;
+  s->kernel_id = d.id;
+  s->tile[GENSOR_DIM_M][0] = d.bm; s->tile[GENSOR_DIM_N][0] = d.bn; s->tile[GENSOR_DIM_K][0] = d.bk;
+  s->tile[GENSOR_DIM_M][1] = d.wm; s->tile[GENSOR_DIM_N][1] = d.wn; s->tile[GENSOR_DIM_K][1] = d.kg;
+  s->vthread[0] = d.vm; s->vthread[1] = d.vn;
+  s->tile[GENSOR_DIM_M][2] = d.wm / d.vm; s->tile[GENSOR_DIM_N][2] = d.wn / d.vn; s->tile[GENSOR_DIM_K][2] = d.kg;
+  s->stages = d.stages;
+  s->unroll = d.bk / d.kg;
+  s->vec_bytes = d.vec ? 16 : (d.in_dtype == GENSOR_F32 ? 4 : 2);
+  s->direct_lds = d.direct;
+  s->split_k = 1;
+  s->wg_remap = 4;
+}
+
+bool instance_serves(const InstanceDesc& d, const GemmView& v) {
+  return d.in_dtype == v.in_dtype && d.out_dtype == v.out_dtype && d.bsrc == v.bsrc;
+}
+
+// Does instance d realise schedule s (same lattice point)?
+static bool instance_matches(const InstanceDesc& d, const gensor_schedule* s) {
+  return d.bm == s->tile[0][0] && d.bn == s->tile[1][0] && d.bk == s->tile[2][0] && d.wm == s->tile[0][1] &&
+         d.wn == s->tile[1][1] && d.kg == s->tile[2][1] && d.vm == s->vthread[0] && d.vn == s->vthread[1] &&
+         d.stages == s->stages && d.direct == s->direct_lds && (d.vec ? 16 : -1) == (s->vec_bytes == 16 ? 16 : -1);
+}
+
+const InstanceDesc* find_instance(const gensor_schedule* s, const GemmView& v) {
+  if (!s || s->version != GENSOR_SCHEDULE_VERSION) return nullptr;
+  if (s->kernel_id >= 0 && s->kernel_id < g_num_instances) {
+    const InstanceDesc& d = g_instances[s->kernel_id];
+    if (instance_serves(d, v) && instance_matches(d, s)) return &d;
+  }
+  for (int i = 0; i < g_num_instances; ++i)
+    if (instance_serves(g_instances[i], v) && instance_matches(g_instances[i], s)) return &g_instances[i];
+  return nullptr;
+}
+
+// Can the 16-byte vector path be used?  (k-contiguous operands need K and their leading
+// dimension to be whole chunks; the n-contiguous operand needs N and ldb to be.)
+bool vector_ok(const GemmView& v, const void* A, int64_t lda, int64_t strideA, const void* B, int64_t ldb, int64_t strideB) {
+  const int epc = 16 / v.esize;
+  auto al = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+  if (!al(A) || lda % epc || strideA % epc || v.K % epc) return false;
+  if (v.bsrc == B_KC) return al(B) && ldb % epc == 0 && strideB % epc == 0;
+  if (v.bsrc == B_NC) return al(B) && ldb % epc == 0 && strideB % epc == 0 && v.N % epc == 0;
+  return true;   // convolution: the gather is element-wise
+}
+
+}  // namespace gensor
+
+extern "C" gensor_status gensor_instance_schedule(int32_t id, const gensor_problem* p, gensor_schedule* out) {
+  if (!p || !out || id < 0 || id >= g_num_instances) return GENSOR_ERR_INVALID_ARG;
+  GemmView v;
+  gensor_status st = gemm_view(p, &v);
+  if (st != GENSOR_OK) return st;
+  if (!instance_serves(g_instances[id], v)) return GENSOR_ERR_UNSUPPORTED;
+  schedule_from_instance(g_instances[id], out);
+  return GENSOR_OK;
+}
+
+extern "C" size_t gensor_workspace_bytes(const gensor_schedule*, const gensor_problem*) { return 0; }
+
+// ------------------------------------------------------------------------------------
+// schedule == NULL: construct once per (problem, alignment class) and remember it.
+// ------------------------------------------------------------------------------------
+namespace {
+std::mutex g_memo_mutex;
+std::map<std::tuple<int, int, int, int, int, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int>, gensor_schedule> g_memo;
+
+gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, gensor_schedule* out) {
+  auto key = std::make_tuple((int)p->op, (int)p->in_dtype, (int)p->out_dtype, (int)p->transB, vec_ok ? 1 : 0,
+                             p->op == GENSOR_OP_CONV2D ? p->n : p->batch, p->op == GENSOR_OP_CONV2D ? p->c : p->M,
+                             p->op == GENSOR_OP_CONV2D ? p->h : p->N, p->op == GENSOR_OP_CONV2D ? p->w : p->K,
+                             p->op == GENSOR_OP_CONV2D ? p->k : 0, p->op == GENSOR_OP_CONV2D ? p->r : 0,
+                             p->op == GENSOR_OP_CONV2D ? p->s : 0,
+                             p->op == GENSOR_OP_CONV2D ? (int)(p->stride * 64 + p->pad) : 0);
+  std::lock_guard<std::mutex> lock(g_memo_mutex);
+  auto it = g_memo.find(key);
+  if (it != g_memo.end()) { *out = it->second; return GENSOR_OK; }
+  gensor_status st = construct_internal(p, nullptr, nullptr, 0, vec_ok, out);
+  if (st == GENSOR_OK) g_memo[key] = *out;
+  return st;
+}
+
+gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmView& v, float alpha,
+                  const void* A, int64_t lda, int64_t strideA, const void* B, int64_t ldb, int64_t strideB,
+                  float beta, void* C, int64_t ldc, int64_t strideC, void* stream) {
+  const bool vec_ok = vector_ok(v, A, lda, strideA, B, ldb, strideB);
+  gensor_schedule local;
+  if (!s) {
+    gensor_status st = memoised_schedule(p, vec_ok, &local);
+    if (st != GENSOR_OK) return st;
+    s = &local;
+  }
+  const InstanceDesc* d = find_instance(s, v);
+  if (!d) return GENSOR_ERR_NO_SCHEDULE;
+  if (d->vec && !vec_ok) return GENSOR_ERR_NO_SCHEDULE;          // schedule asks for vector accesses the operands cannot give
+  if (d->direct && v.K % d->bk != 0) return GENSOR_ERR_NO_SCHEDULE;
+  if (s->split_k > 1) return GENSOR_ERR_UNSUPPORTED;
+
+  KernelArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.A = A; a.B = B; a.C = C;
+  a.M = (int32_t)v.M; a.N = (int32_t)v.N; a.K = (int32_t)v.K;
+  a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+  a.strideA = strideA; a.strideB = strideB; a.strideC = strideC;
+  a.alpha = alpha; a.beta = beta;
+  a.tiles_m = (int32_t)((v.M + d->bm - 1) / d->bm);
+  a.tiles_n = (int32_t)((v.N + d->bn - 1) / d->bn);
+  a.batch = (int32_t)v.batch;
+  a.panel = s->wg_remap > 0 ? s->wg_remap : 1;
+  if (a.panel > a.tiles_m) a.panel = a.tiles_m;
+  if ((int64_t)a.tiles_m * a.tiles_n * a.batch > INT32_MAX) return GENSOR_ERR_UNSUPPORTED;
+  if (v.bsrc == B_CONV) {
+    a.cC = (int32_t)p->c; a.cH = (int32_t)p->h; a.cW = (int32_t)p->w; a.cR = (int32_t)p->r; a.cS = (int32_t)p->s;
+    a.cP = (int32_t)v.P; a.cQ = (int32_t)v.Q; a.cStride = (int32_t)p->stride; a.cPad = (int32_t)p->pad;
+  }
+  hipError_t e = d->launch(a, (hipStream_t)stream);
+  return e == hipSuccess ? GENSOR_OK : GENSOR_ERR_DEVICE;
+}
+}  // namespace
+
+extern "C" gensor_status gensor_bmm(const gensor_schedule* s, const gensor_problem* p, float alpha,
+                                    const void* A, int64_t lda, int64_t strideA,
+                                    const void* B, int64_t ldb, int64_t strideB,
+                                    float beta, void* C, int64_t ldc, int64_t strideC,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (!p || !A || !B || !C) return GENSOR_ERR_INVALID_ARG;
+  if (p->op != GENSOR_OP_GEMM && p->op != GENSOR_OP_BMM) return GENSOR_ERR_INVALID_ARG;
+  GemmView v;
+  gensor_status st = gemm_view(p, &v);
+  if (st != GENSOR_OK) return st;
+  if (lda < v.K) return GENSOR_ERR_INVALID_ARG;
+  if (ldb < (v.bsrc == B_KC ? v.K : v.N)) return GENSOR_ERR_INVALID_ARG;
+  if (ldc < v.N) return GENSOR_ERR_INVALID_ARG;
+  if (strideA < 0 || strideB < 0 || strideC < 0) return GENSOR_ERR_INVALID_ARG;
+  if (v.batch > 1 && strideC < v.M * ldc - (ldc - v.N)) return GENSOR_ERR_INVALID_ARG;   // outputs must not overlap
+  return run(s, p, v, alpha, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC, hip_stream);
+}
+
+extern "C" gensor_status gensor_gemm(const gensor_schedule* s, const gensor_problem* p, float alpha,
+                                     const void* A, int64_t lda, const void* B, int64_t ldb,
+                                     float beta, void* C, int64_t ldc,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!p || p->op != GENSOR_OP_GEMM) return GENSOR_ERR_INVALID_ARG;
+  return gensor_bmm(s, p, alpha, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" gensor_status gensor_conv2d(const gensor_schedule* s, const gensor_problem* p,
+                                       const void* input, const void* weight, void* output,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (!p || !input || !weight || !output || p->op != GENSOR_OP_CONV2D) return GENSOR_ERR_INVALID_ARG;
+  GemmView v;
+  gensor_status st = gemm_view(p, &v);
+  if (st != GENSOR_OK) return st;
+  if (p->n * p->c * p->h * p->w > INT32_MAX) { /* index arithmetic of the gather is 64-bit; extents are 32-bit */ }
+  // A = filters [k][c*r*s] (k-contiguous), B = gathered input, C = output viewed per image.
+  return run(s, p, v, 1.0f, weight, v.K, 0, input, 0, 0, 0.0f, output, v.N, 0, hip_stream);
+}

@@ -1,0 +1,27 @@
+// Host-side declarations shared by the operator entry points and the constructor.
+#pragma once
+#include <stdint.h>
+
+#include "../../include/gensor.h"
+#include "registry.hpp"
+
+namespace gensor {
+
+// GEMM view of a problem: C[M][N] += A[M][K] * B[K][N] per batch.
+struct GemmView {
+  int64_t M, N, K, batch;
+  int64_t P, Q;          // convolution output extent
+  int in_dtype, out_dtype, esize, osize;
+  int bsrc;              // BSrc
+};
+
+gensor_status gemm_view(const gensor_problem* p, GemmView* v);
+void schedule_from_instance(const InstanceDesc& d, gensor_schedule* s);
+bool instance_serves(const InstanceDesc& d, const GemmView& v);
+const InstanceDesc* find_instance(const gensor_schedule* s, const GemmView& v);
+
+// gensor_construct with one more input: whether the operands allow 16-byte vector accesses.
+gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
+                                 uint64_t seed, bool vec_ok, gensor_schedule* out);
+
+}  // namespace gensor

@@ -1,0 +1,73 @@
+"""The compiled part of the schedule lattice: which (tile, wave tile, MFMA block, virtual
+thread, staging) points exist as kernel instances for each element type and operand source.
+build.py turns this list into one translation unit per instance plus the registry table."""
+from itertools import product
+
+DT = {"f32": 0, "f16": 1, "bf16": 2}
+BSRC = {"KC": 0, "NC": 1, "CONV": 2}
+CT = {"f32": "f32_t", "f16": "f16_t", "bf16": "bf16_t"}
+
+
+def _inst(dt, out, bm, bn, bk, wm, wn, mb, vm=1, vn=1, bsrc="KC", vec=1, stages=2, direct=0):
+    return dict(dt=dt, out=out, bm=bm, bn=bn, bk=bk, wm=wm, wn=wn, mb=mb, vm=vm, vn=vn,
+                bsrc=bsrc, vec=vec, stages=stages, direct=direct)
+
+
+def lattice():
+    out = []
+    # 16-bit inputs, fp32 output: (BM, BN, BK, WM, WN, MB, VM, VN)
+    tiles16 = [
+        (256, 256, 64, 128, 128, 32, 1, 1),
+        (256, 128, 64, 128, 64, 32, 1, 1),
+        (128, 256, 64, 64, 128, 32, 1, 1),
+        (128, 128, 64, 64, 64, 32, 1, 1),
+        (128, 128, 64, 64, 64, 32, 2, 2),
+        (128, 128, 64, 64, 64, 16, 1, 1),
+        (128, 64, 64, 64, 32, 32, 1, 1),
+        (64, 128, 64, 32, 64, 32, 1, 1),
+        (64, 64, 64, 32, 32, 32, 1, 1),
+        (64, 64, 64, 32, 32, 16, 1, 1),
+        (32, 32, 64, 16, 16, 16, 1, 1),
+    ]
+    for dt in ("f16", "bf16"):
+        for bsrc in ("KC", "NC", "CONV"):
+            for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles16:
+                out.append(_inst(dt, "f32", bm, bn, bk, wm, wn, mb, vm, vn, bsrc))
+            # scalar-access instance: any alignment, any extents
+            out.append(_inst(dt, "f32", 64, 64, 32, 32, 32, 16, 1, 1, bsrc, vec=0))
+        # direct global->LDS staging for k-contiguous operands
+        out.append(_inst(dt, "f32", 256, 256, 64, 128, 128, 32, 1, 1, "KC", direct=1))
+        out.append(_inst(dt, "f32", 128, 128, 64, 64, 64, 32, 1, 1, "KC", direct=1))
+        # 16-bit output variants
+        out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "KC"))
+        out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "NC"))
+        out.append(_inst(dt, dt, 64, 64, 32, 32, 32, 16, 1, 1, "KC", vec=0))
+        out.append(_inst(dt, dt, 64, 64, 32, 32, 32, 16, 1, 1, "NC", vec=0))
+        out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "CONV"))
+        out.append(_inst(dt, dt, 64, 64, 32, 32, 32, 16, 1, 1, "CONV", vec=0))
+    tiles32 = [
+        (128, 128, 32, 64, 64, 32, 1, 1),
+        (128, 128, 32, 64, 64, 32, 2, 2),
+        (64, 64, 32, 32, 32, 32, 1, 1),
+        (64, 64, 32, 32, 32, 16, 1, 1),
+        (32, 32, 32, 16, 16, 16, 1, 1),
+        (64, 32, 32, 32, 16, 16, 1, 1),
+    ]
+    for bsrc in ("KC", "NC", "CONV"):
+        for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles32:
+            out.append(_inst("f32", "f32", bm, bn, bk, wm, wn, mb, vm, vn, bsrc))
+        out.append(_inst("f32", "f32", 64, 64, 16, 32, 32, 16, 1, 1, bsrc, vec=0))
+    for i, d in enumerate(out):
+        d["id"] = i
+    return out
+
+
+def cfg_type(d):
+    return ("Cfg<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s, %d, %s>" % (
+        CT[d["dt"]], CT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"], d["vm"], d["vn"],
+        BSRC[d["bsrc"]], "true" if d["vec"] else "false", d["stages"], "true" if d["direct"] else "false"))
+
+
+if __name__ == "__main__":
+    L = lattice()
+    print(len(L), "instances")

@@ -1,0 +1,37 @@
+// Table of the ahead-of-time compiled kernel instances: the finite part of the schedule
+// lattice that exists as machine code.  Each entry is one point (tiles, virtual threads,
+// staging mode, vector width) for one element type and operand source.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "gemm_kernel.hpp"
+
+namespace gensor {
+
+struct InstanceDesc {
+  int id;
+  int in_dtype, out_dtype;              // gensor_dtype values
+  int bm, bn, bk, wm, wn, mb, vm, vn;
+  int bsrc;                             // BSrc
+  int vec, stages, direct;
+  int lds_bytes, threads, kg;           // kg: k consumed per fragment read
+  hipError_t (*launch)(const KernelArgs&, hipStream_t);
+};
+
+extern const InstanceDesc g_instances[];
+extern const int g_num_instances;
+
+template <typename C>
+hipError_t launch_instance(const KernelArgs& a, hipStream_t st) {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)contraction_kernel<C>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.batch;
+  hipLaunchKernelGGL(contraction_kernel<C>, dim3(grid), dim3(C::THREADS), C::LDS_BYTES, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace gensor

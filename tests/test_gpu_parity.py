@@ -1,0 +1,194 @@
+"""GPU parity: the HIP kernels, called through the C ABI, against the CPU oracle.
+
+Integer-valued inputs make every partial sum exact in fp32, so any summation order must
+agree with the oracle bit for bit; real-valued inputs are held to the stated tolerances
+(relative Frobenius error <= 1e-5 for fp32, <= 2e-3 for fp16/bf16 inputs with fp32 accumulate).
+"""
+import numpy as np
+import pytest
+
+from oracle import ops
+from paper_2502_11407_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}
+DT_NAME = {0: "f32", 1: "f16", 2: "bf16"}
+
+
+@pytest.fixture(scope="module")
+def gs():
+    from paper_2502_11407_amd import binding
+    return binding
+
+
+def _round_up(x, m):
+    return (x + m - 1) // m * m
+
+
+def run_gemm(gs, dtype, M, N, K, transB, sched, A, B, alpha=1.0, beta=0.0, C0=None, batch=1, out_dtype="f32"):
+    import torch
+    p = gs.gemm_problem(dtype, M, N, K, 0, transB, batch, out_dtype)
+    dA, dB = gs.to_device(A, dtype), gs.to_device(B, dtype)
+    shape = (batch, M, N) if batch > 1 else (M, N)
+    if C0 is None:
+        dC = torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")   # beta = 0 must not read it
+        if out_dtype != "f32":
+            dC = dC.to({"f16": torch.float16, "bf16": torch.bfloat16}[out_dtype])
+    else:
+        dC = gs.to_device(C0, out_dtype)
+    if batch > 1:
+        gs.bmm(p, dA, dB, dC, alpha, beta, sched)
+    else:
+        gs.gemm(p, dA, dB, dC, alpha, beta, sched)
+    torch.cuda.synchronize()
+    return gs.to_host_f64(dC)
+
+
+def instance_cases(gs):
+    """(instance id, dtype, bsrc, vec, direct, bm, bn, bk) for every compiled instance."""
+    out = []
+    for idx in range(gs.num_instances()):
+        for dt in ("f32", "f16", "bf16"):
+            for out_dt in sorted({"f32", dt}):
+                for tb, op in ((1, "gemm"), (0, "gemm"), (0, "conv")):
+                    p = (gs.conv_problem(dt, 1, 8, 8, 8, 8, 3, 3, 1, 1, out_dt) if op == "conv"
+                         else gs.gemm_problem(dt, 64, 64, 64, 0, tb, 1, out_dt))
+                    s = gs.instance_schedule(idx, p)
+                    if s is not None:
+                        out.append((idx, dt, out_dt, op, tb, s))
+    return out
+
+
+def test_every_instance_bit_exact_on_integers(gs):
+    """Each compiled instance on a problem with several tiles and ragged tails in m, n and k."""
+    cases = instance_cases(gs)
+    assert len(cases) == gs.num_instances()
+    for (idx, dt, out_dt, op, tb, s) in cases:
+        bm, bn, bk = s.tile[0][0], s.tile[1][0], s.tile[2][0]
+        epc = 4 if dt == "f32" else 8
+        vec = s.vec_bytes == 16
+        print(f"instance {idx} {dt}->{out_dt} {op} transB={tb} tile {bm}x{bn}x{bk} vec={vec} direct={s.direct_lds}", flush=True)
+        lim = 1 if out_dt == "bf16" else 4      # keep results exactly representable in the output type
+        if op == "gemm":
+            M = bm + 17
+            N = bn + (8 if vec else 9)
+            K = 2 * bk + (0 if s.direct_lds else (epc if vec else 5))
+            A = inputs.small_ints(100 + idx, (M, K), dt, -lim, lim)
+            B = inputs.small_ints(200 + idx, (N, K) if tb else (K, N), dt, -lim, lim)
+            want = ops.gemm(A, B, dt, transB=tb)
+            got = run_gemm(gs, dt, M, N, K, tb, s, A, B, out_dtype=out_dt)
+        else:
+            import torch
+            c, r = (8, 3) if vec else (5, 3)        # K = c*r*r: 72 (whole chunks) or 45
+            k = bm + 5
+            n, h, w = 2, 9, max(7, bn // 8)
+            I = inputs.small_ints(300 + idx, (n, c, h, w), dt, -min(lim, 2), min(lim, 2))
+            W = inputs.small_ints(400 + idx, (k, c, r, r), dt, -min(lim, 2), min(lim, 2))
+            want = ops.conv2d(I, W, dt, stride=1, pad=1)
+            p = gs.conv_problem(dt, n, c, h, w, k, r, r, 1, 1, out_dt)
+            dO = gs.empty_device(want.shape, out_dt)
+            dO.fill_(float("nan"))
+            gs.conv2d(p, gs.to_device(I, dt), gs.to_device(W, dt), dO, s)
+            torch.cuda.synchronize()
+            got = gs.to_host_f64(dO)
+        assert np.abs(want).max() < (256 if out_dt == "bf16" else 2048)
+        assert np.array_equal(got, want), f"instance {idx}: max abs diff {np.abs(got - want).max()}"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("transB", [0, 1])
+def test_gemm_real_values_default_schedule(gs, dtype, transB):
+    M, N, K = 300, 264, 520
+    A = inputs.uniform_pm1(1, (M, K), dtype)
+    B = inputs.uniform_pm1(2, (N, K) if transB else (K, N), dtype)
+    want = ops.gemm(A, B, dtype, transB=transB)
+    got = run_gemm(gs, dtype, M, N, K, transB, None, A, B)
+    err = ops.rel_frobenius(got, want)
+    print(dtype, transB, "rel frobenius", err)
+    assert err <= TOL[dtype]
+    assert err <= 1e-5      # rounding alone is ~1e-7..1e-6 (see the CPU error-bound test)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_gemm_alpha_beta_and_unaligned_shapes(gs, dtype):
+    M, N, K = 77, 53, 41        # nothing is a multiple of a chunk: scalar path
+    A = inputs.small_ints(3, (M, K), dtype)
+    B = inputs.small_ints(4, (K, N), dtype)
+    C0 = inputs.small_ints(5, (M, N), "f32")
+    want = ops.gemm(A, B, dtype, alpha=2.0, beta=-3.0, C0=C0)
+    got = run_gemm(gs, dtype, M, N, K, 0, None, A, B, alpha=2.0, beta=-3.0, C0=C0)
+    assert np.array_equal(got, want)
+    got1 = run_gemm(gs, dtype, M, N, K, 0, None, A, B, alpha=0.0, beta=1.0, C0=C0)
+    assert np.array_equal(got1, C0)
+
+
+def test_gemm_degenerate_extents(gs):
+    for (M, N, K) in [(1, 1, 1), (1, 300, 7), (300, 1, 8), (5, 5, 1024), (130, 2, 3)]:
+        A = inputs.small_ints(6, (M, K), "f16")
+        B = inputs.small_ints(7, (N, K), "f16")
+        assert np.array_equal(run_gemm(gs, "f16", M, N, K, 1, None, A, B), ops.gemm(A, B, "f16", transB=1)), (M, N, K)
+
+
+def test_bmm_strided_batches(gs):
+    w = inputs.config4_bmm_scores(batch=5, seq=200, head=64)
+    want = ops.bmm(w.A, w.B, "f16", transB=1, alpha=0.125)
+    got = run_gemm(gs, "f16", 200, 200, 64, 1, None, w.A, w.B, alpha=0.125, batch=5)
+    assert ops.rel_frobenius(got, want) <= 1e-5
+    wt = inputs.config4_bmm_scores(batch=5, seq=200, head=64, materialised_kt=True)
+    got2 = run_gemm(gs, "f16", 200, 200, 64, 0, None, wt.A, wt.B, alpha=0.125, batch=5)
+    assert ops.rel_frobenius(got2, want) <= 1e-5
+
+
+@pytest.mark.parametrize("which,n,hw", [("3x3", 2, 20), ("1x1s2", 2, 14)])
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_conv_real_values(gs, which, n, hw, dtype):
+    import torch
+    w = inputs.config5_conv(which, n=n, dtype=dtype, hw=hw)
+    want = ops.conv2d(w.I, w.W, dtype, stride=w.stride, pad=w.pad)
+    p = gs.conv_problem(dtype, w.n, w.c, w.h, w.w, w.k, w.r, w.s, w.stride, w.pad)
+    dO = gs.empty_device(want.shape)
+    dO.fill_(float("nan"))
+    gs.conv2d(p, gs.to_device(w.I, dtype), gs.to_device(w.W, dtype), dO)
+    torch.cuda.synchronize()
+    err = ops.rel_frobenius(gs.to_host_f64(dO), want)
+    print(which, dtype, "rel frobenius", err)
+    assert err <= min(TOL[dtype], 1e-5)
+
+
+@pytest.mark.parametrize("stride,pad,r,s", [(1, 0, 3, 3), (2, 1, 3, 3), (2, 2, 5, 3), (3, 0, 1, 1), (1, 2, 1, 5)])
+def test_conv_geometry_bit_exact(gs, stride, pad, r, s):
+    import torch
+    n, c, h, w, k = 3, 6, 13, 11, 10
+    I = inputs.small_ints(8, (n, c, h, w), "f16", -2, 2)
+    W = inputs.small_ints(9, (k, c, r, s), "f16", -2, 2)
+    want = ops.conv2d(I, W, "f16", stride=stride, pad=pad)
+    p = gs.conv_problem("f16", n, c, h, w, k, r, s, stride, pad)
+    dO = gs.empty_device(want.shape)
+    gs.conv2d(p, gs.to_device(I, "f16"), gs.to_device(W, "f16"), dO)
+    torch.cuda.synchronize()
+    assert np.array_equal(gs.to_host_f64(dO), want)
+
+
+def test_error_paths_launch_nothing(gs):
+    import torch
+    p = gs.gemm_problem("f16", 64, 64, 64, 0, 1)
+    A = torch.zeros((64, 64), dtype=torch.float16, device="cuda")
+    Cc = torch.zeros((64, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(gs.GensorError) as e:
+        gs.gemm(p, A, A, Cc, lda=32)           # leading dimension smaller than the row
+    assert e.value.status == 1
+    bad = gs.gemm_problem("f16", 0, 64, 64, 0, 1)
+    with pytest.raises(gs.GensorError) as e:
+        gs.gemm(bad, A, A, Cc)
+    assert e.value.status == 1
+    pt = gs.gemm_problem("f16", 64, 64, 64, 1, 1)     # transposed A has no kernel
+    with pytest.raises(gs.GensorError) as e:
+        gs.gemm(pt, A, A, Cc)
+    assert e.value.status == 2
+    s = gs.instance_schedule(0, p)
+    s.tile[0][0] = 48                                  # not a lattice point
+    s.kernel_id = -1
+    with pytest.raises(gs.GensorError) as e:
+        gs.gemm(p, A, A, Cc, schedule=s)
+    assert e.value.status == 3
