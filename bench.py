@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the scheduled dense operators on one MI355X.
+
+One JSON line on stdout.  A "step" is one launch of the headline operator: the fp16 GEMM
+M=N=K=4096 (fp32 accumulate and output, A row-major, B column-major) with the schedule
+gensor_construct picked for it; inputs are resident in HBM before the timed region.
+`value` is its TFLOP/s.  The same line carries
+  roofline      dense fp16 MFMA peak against the measured kernel time (HIP events on the
+                stream the kernel runs on)
+  cpu_baseline  the CPU oracle timed on a bounded slice of the same GEMM
+  operators     every other benchmark shape (fp32 GEMM, GPT-2 GEMMs, attention-score
+                BMM, ResNet-50 convolutions) timed the same way, with schedule-construction
+                wall time and a sampled parity error against the oracle
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "f32": 157.3}   # dense MFMA, MI355X
+HBM_GBS = 8000.0
+
+
+def _algorithmic_bytes(w, gs_inputs):
+    es = 4 if w.dtype == "f32" else 2
+    if isinstance(w, gs_inputs.GemmWorkload):
+        return w.batch * (es * (w.M * w.K + w.K * w.N) + 4 * w.M * w.N)
+    return es * (w.n * w.c * w.h * w.w + w.k * w.c * w.r * w.s) + 4 * w.n * w.k * w.p * w.q
+
+
+class Case:
+    """One workload resident on the device with its constructed schedule."""
+
+    def __init__(self, gs, inputs, w):
+        import torch
+        self.gs, self.w = gs, w
+        self.is_gemm = isinstance(w, inputs.GemmWorkload)
+        if self.is_gemm:
+            self.p = gs.gemm_problem(w.dtype, w.M, w.N, w.K, w.transA, w.transB, w.batch)
+            self.a, self.b = gs.to_device(w.A, w.dtype), gs.to_device(w.B, w.dtype)
+            self.out = gs.empty_device((w.batch, w.M, w.N) if w.batch > 1 else (w.M, w.N))
+        else:
+            self.p = gs.conv_problem(w.dtype, w.n, w.c, w.h, w.w, w.k, w.r, w.s, w.stride, w.pad)
+            self.a, self.b = gs.to_device(w.I, w.dtype), gs.to_device(w.W, w.dtype)
+            self.out = gs.empty_device((w.n, w.k, w.p, w.q))
+        t0 = time.perf_counter()
+        self.sched = gs.construct(self.p, seed=0)
+        self.construct_s = time.perf_counter() - t0
+        torch.cuda.synchronize()
+
+    def launch(self):
+        gs, w = self.gs, self.w
+        if not self.is_gemm:
+            gs.conv2d(self.p, self.a, self.b, self.out, self.sched)
+        elif w.batch > 1:
+            gs.bmm(self.p, self.a, self.b, self.out, 1.0, 0.0, self.sched)
+        else:
+            gs.gemm(self.p, self.a, self.b, self.out, 1.0, 0.0, self.sched)
+
+    def time_ms(self, steps, warmup):
+        """Average launch duration from HIP events recorded on the launch stream."""
+        import torch
+        for _ in range(warmup):
+            self.launch()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            self.launch()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        return e0.elapsed_time(e1) / steps, wall_ms
+
+    def parity(self, samples=512):
+        """Relative Frobenius error against the oracle on sampled output coordinates."""
+        import torch
+        from oracle import ops
+        from paper_2502_11407_amd import inputs
+        w = self.w
+        self.launch()
+        torch.cuda.synchronize()
+        if self.is_gemm:
+            co = inputs.sample_indices(7, (w.batch, w.M, w.N), samples)
+            want = ops.bmm_at(w.A, w.B, w.dtype, co, transA=w.transA, transB=w.transB)
+            out = self.out if w.batch > 1 else self.out[None]
+            idx = torch.from_numpy(co).cuda()
+            got = out[idx[:, 0], idx[:, 1], idx[:, 2]]
+        else:
+            co = inputs.sample_indices(7, (w.n, w.k, w.p, w.q), samples)
+            want = ops.conv2d_at(w.I, w.W, w.dtype, co, stride=w.stride, pad=w.pad)
+            idx = torch.from_numpy(co).cuda()
+            got = self.out[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+        return ops.rel_frobenius(got.double().cpu().numpy(), want)
+
+
+def cpu_baseline(w):
+    """The oracle as it stands on a bounded slice (leading rows of A) of the headline GEMM."""
+    from oracle import ops
+    rows = 2 * ops.num_threads()
+    t0 = time.perf_counter()
+    ops.gemm(w.A[:rows], w.B, w.dtype, transA=w.transA, transB=w.transB)
+    dt = time.perf_counter() - t0
+    target = 12.0
+    rows2 = int(min(w.M, max(rows, rows * target / max(dt, 1e-3))))
+    rows2 = max(ops.num_threads(), rows2 - rows2 % ops.num_threads())
+    t0 = time.perf_counter()
+    ops.gemm(w.A[:rows2], w.B, w.dtype, transA=w.transA, transB=w.transB)
+    dt = time.perf_counter() - t0
+    flops = 2.0 * rows2 * w.N * w.K
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": ops.num_threads(), "kind": "oracle",
+            "sample": f"first {rows2} of {w.M} rows of C (all {w.N} columns, full K={w.K}), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--only-headline", action="store_true", help="skip the other operator shapes and the CPU legs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (single-GPU operators, "
+              "no collectives)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from paper_2502_11407_amd import binding as gs, inputs
+
+    w = inputs.config2_gemm_f16()
+    head = Case(gs, inputs, w)
+    ms, wall_ms = head.time_ms(args.steps, args.warmup)
+    tflops = w.flops / (ms * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[w.dtype]
+    line = {
+        "metric": "TFLOP/s and % of MFMA peak per operator on 1 MI355X; construction time (s)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "GEMM fp16 in / fp32 accumulate+out, M=N=K=4096, A row-major, B column-major, "
+                               "uniform[-1,1) (configs[1])",
+                   "schedule": head.sched.describe()},
+        "pct_of_mfma_peak": 100.0 * tflops / peak,
+        "construct_s": head.construct_s,
+        "wall_ms_per_step": wall_ms,
+        "roofline": {"bound": "mfma", "achieved": tflops, "peak": peak, "unit": "TFLOP/s",
+                     "frac": tflops / peak, "traffic": None},
+    }
+    if not args.only_headline:
+        line["parity_rel_frobenius_sampled"] = head.parity()
+        ops_out = []
+        steps2 = max(10, args.steps // 4)
+        for name, wl in inputs.all_configs().items():
+            if name == "cfg2":
+                continue
+            c = Case(gs, inputs, wl)
+            m, _ = c.time_ms(steps2, max(3, args.warmup // 4))
+            tf = wl.flops / (m * 1e-3) / 1e12
+            gb = _algorithmic_bytes(wl, inputs) / (m * 1e-3) / 1e9
+            ops_out.append({"workload": wl.name, "dtype": wl.dtype, "us": m * 1e3, "tflops": tf,
+                            "pct_of_mfma_peak": 100.0 * tf / PEAK_TFLOPS[wl.dtype],
+                            "algorithmic_GBs": gb, "pct_of_hbm_peak": 100.0 * gb / HBM_GBS,
+                            "construct_s": c.construct_s, "kernel_id": c.sched.kernel_id,
+                            "parity_rel_frobenius_sampled": c.parity(256)})
+            del c
+            torch.cuda.empty_cache()
+        line["operators"] = ops_out
+        line["cpu_baseline"] = cpu_baseline(w)
+        line["paper_context"] = ("paper (RTX 4090, precision not stated): GEMM 45.2 TFLOP/s, Conv2d C1 34.54 TFLOP/s, "
+                                 "construction 'a few seconds' (Table VI, Fig. 8 caption)")
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
