@@ -228,11 +228,68 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 #pragma unroll
       for (int v = 0; v < MF::NACC; ++v) acc[i][j][v] = 0.f;
 
+  // ---- buffer resources.  Each operand is addressed through a buffer descriptor whose
+  // base is this workgroup's first row (or column) at the current k tile and whose extent
+  // ends with the matrix: out-of-range lanes read zero (or are dropped on store) in
+  // hardware, so the loop body has no branches.  Offsets inside a tile stay below 2^31 (the
+  // host checks BM * lda, BN * ldb or BK * ldb, and BM * ldc).
+  constexpr uint32_t RSRC_FLAGS = 0x00020000u;
+  constexpr uint32_t OOB = 0x80000000u;      // beyond every descriptor (extents are clamped below 2^31)
+  auto clamp_records = [](int64_t bytes) -> uint32_t {
+    return bytes <= 0 ? 0u : (bytes > 0x7fffffffll ? 0x7fffffffu : (uint32_t)bytes);
+  };
+  const int rows_valid = min(BM, args.M - m0);
+  const int cols_valid = min(BN, args.N - n0);
+  const char* a_tile = Ab + (int64_t)m0 * args.lda * ES;
+  const char* b_tile = (C::BSRC == B_KC) ? Bb + (int64_t)n0 * args.ldb * ES : Bb + (int64_t)n0 * ES;
+  auto rsrc_a = [&](int k0) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(a_tile + (int64_t)k0 * ES), 0,
+        clamp_records(((int64_t)(rows_valid - 1) * args.lda + (args.K - k0)) * ES), RSRC_FLAGS);
+  };
+  auto rsrc_b = [&](int k0) {
+    if constexpr (C::BSRC == B_KC)
+      return __builtin_amdgcn_make_buffer_rsrc((void*)(b_tile + (int64_t)k0 * ES), 0,
+          clamp_records(((int64_t)(cols_valid - 1) * args.ldb + (args.K - k0)) * ES), RSRC_FLAGS);
+    else
+      return __builtin_amdgcn_make_buffer_rsrc((void*)(b_tile + (int64_t)k0 * args.ldb * ES), 0,
+          clamp_records(((int64_t)(args.K - k0 - 1) * args.ldb + (args.N - n0)) * ES), RSRC_FLAGS);
+  };
+
+  // ---- who loads what.  A thread owns LDS chunk slots q = tid + i*THREADS of a
+  // k-contiguous tile (slot q = row q/CPR, physical chunk q%CPR) and fetches the logical
+  // chunk that the swizzle maps there; the same ownership serves the register-staged and
+  // the direct path (a direct load deposits lane l's 16 bytes at slot base + l).
+  constexpr bool SCALAR_A = !C::VEC;
+  constexpr bool SCALAR_B = !C::VEC || C::BSRC == B_CONV;
+  uint32_t a_voff[C::A_LOADS], a_kch[C::A_LOADS];
+#pragma unroll
+  for (int i = 0; i < C::A_LOADS; ++i) {
+    const int q = tid + i * C::THREADS;
+    const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::CPR);
+    a_voff[i] = (uint32_t)((row * (int)args.lda + ch * EPC) * ES);
+    a_kch[i] = ch * EPC;
+  }
+  uint32_t b_voff[C::B_LOADS], b_kch[C::B_LOADS];
+#pragma unroll
+  for (int i = 0; i < C::B_LOADS; ++i) {
+    const int q = tid + i * C::THREADS;
+    if constexpr (C::BSRC == B_KC) {
+      const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::CPR);
+      b_voff[i] = (uint32_t)((row * (int)args.ldb + ch * EPC) * ES);
+      b_kch[i] = ch * EPC;
+    } else {
+      constexpr int CPRN = BN * ES / 16;
+      const int krow = q / CPRN, ch = q % CPRN;
+      b_voff[i] = (uint32_t)((krow * (int)args.ldb + ch * EPC) * ES);
+      b_kch[i] = krow;
+    }
+  }
+
   // ---- staging registers (global -> registers -> LDS)
   u32x4 ra[C::DIRECT ? 1 : C::A_LOADS];
   u32x4 rb[C::DIRECT ? 1 : C::B_LOADS];
 
-  // element (row, k) of A / element (k, col) of B as float-convertible scalars, for the scalar path
+  // element-wise access for the scalar path and the convolution gather
   auto a_elem_bits = [&](int row, int k) -> uint32_t {
     if (row < args.M && k < args.K) {
       int64_t idx = (int64_t)row * args.lda + k;
@@ -270,104 +327,95 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     return v;
   };
 
-  // ---- global -> registers for the k-tile starting at k0
-  auto load_a = [&](int k0) {
+  // ---- fetch the k tile starting at k0: into registers, or straight into LDS stage `st`.
+  // In a k-contiguous row a chunk beyond K would alias the next row, so those lanes are
+  // sent out of range; this can only happen in the last k tile.
+  auto fetch_a = [&](int k0, int st) {
+    const bool full = args.K - k0 >= BK;
+    if constexpr (SCALAR_A) {
 #pragma unroll
-    for (int i = 0; i < C::A_LOADS; ++i) {
-      const int q = tid + i * C::THREADS;
-      if (C::A_CHUNKS % C::THREADS != 0 && q >= C::A_CHUNKS) break;
-      const int row = q / C::CPR, ch = q % C::CPR;
-      const int gm = m0 + row, gk = k0 + ch * EPC;
-      if constexpr (C::VEC) {
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (gm < args.M && gk < args.K) v = *(const u32x4*)(Ab + ((int64_t)gm * args.lda + gk) * ES);
-        ra[i] = v;
-      } else {
-        ra[i] = pack_chunk([&](int e) { return a_elem_bits(gm, gk + e); });
+      for (int i = 0; i < C::A_LOADS; ++i) {
+        const int q = tid + i * C::THREADS;
+        if (C::A_CHUNKS % C::THREADS != 0 && q >= C::A_CHUNKS) break;
+        const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::CPR);
+        ra[i] = pack_chunk([&](int e) { return a_elem_bits(m0 + row, k0 + ch * EPC + e); });
+      }
+    } else {
+      const __amdgpu_buffer_rsrc_t r = rsrc_a(k0);
+#pragma unroll
+      for (int i = 0; i < C::A_LOADS; ++i) {
+        if (C::A_CHUNKS % C::THREADS != 0 && tid + i * C::THREADS >= C::A_CHUNKS) break;
+        const uint32_t off = (full || (int)a_kch[i] < args.K - k0) ? a_voff[i] : OOB;
+        if constexpr (C::DIRECT)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (GENSOR_LDS void*)(lds + st * C::STAGE_BYTES + (i * C::THREADS + wave * 64) * 16),
+                                                   16, off, 0, 0, 0);
+        else
+          ra[i] = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
       }
     }
   };
-  auto load_b = [&](int k0) {
+  auto fetch_b = [&](int k0, int st) {
+    const bool full = args.K - k0 >= BK;
+    if constexpr (SCALAR_B) {
 #pragma unroll
-    for (int i = 0; i < C::B_LOADS; ++i) {
-      const int q = tid + i * C::THREADS;
-      if (C::B_CHUNKS % C::THREADS != 0 && q >= C::B_CHUNKS) break;
-      if constexpr (C::BSRC == B_KC) {
-        const int row = q / C::CPR, ch = q % C::CPR;
-        const int gn = n0 + row, gk = k0 + ch * EPC;
-        if constexpr (C::VEC) {
-          u32x4 v = {0u, 0u, 0u, 0u};
-          if (gn < args.N && gk < args.K) v = *(const u32x4*)(Bb + ((int64_t)gn * args.ldb + gk) * ES);
-          rb[i] = v;
+      for (int i = 0; i < C::B_LOADS; ++i) {
+        const int q = tid + i * C::THREADS;
+        if (C::B_CHUNKS % C::THREADS != 0 && q >= C::B_CHUNKS) break;
+        if constexpr (C::BSRC == B_KC) {
+          const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::CPR);
+          rb[i] = pack_chunk([&](int e) { return b_elem_bits(k0 + ch * EPC + e, n0 + row); });
         } else {
-          rb[i] = pack_chunk([&](int e) { return b_elem_bits(gk + e, gn); });
+          constexpr int CPRN = BN * ES / 16;
+          const int krow = q / CPRN, ch = q % CPRN;
+          rb[i] = pack_chunk([&](int e) { return b_elem_bits(k0 + krow, n0 + ch * EPC + e); });
         }
-      } else {
-        constexpr int CPRN = BN * ES / 16;
-        const int krow = q / CPRN, ch = q % CPRN;
-        const int gk = k0 + krow, gn = n0 + ch * EPC;
-        if constexpr (C::VEC && C::BSRC == B_NC) {
-          u32x4 v = {0u, 0u, 0u, 0u};
-          if (gk < args.K && gn < args.N) v = *(const u32x4*)(Bb + ((int64_t)gk * args.ldb + gn) * ES);
-          rb[i] = v;
-        } else {
-          rb[i] = pack_chunk([&](int e) { return b_elem_bits(gk, gn + e); });
-        }
+      }
+    } else {
+      const __amdgpu_buffer_rsrc_t r = rsrc_b(k0);
+#pragma unroll
+      for (int i = 0; i < C::B_LOADS; ++i) {
+        if (C::B_CHUNKS % C::THREADS != 0 && tid + i * C::THREADS >= C::B_CHUNKS) break;
+        uint32_t off = b_voff[i];
+        if constexpr (C::BSRC == B_KC) off = (full || (int)b_kch[i] < args.K - k0) ? off : OOB;
+        if constexpr (C::DIRECT)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (GENSOR_LDS void*)(lds + st * C::STAGE_BYTES + C::A_BYTES + (i * C::THREADS + wave * 64) * 16),
+                                                   16, off, 0, 0, 0);
+        else
+          rb[i] = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
       }
     }
   };
   // ---- registers -> LDS stage `st`
-  auto store_a = [&](int st) {
-    GENSOR_LDS char* base = lds + st * C::STAGE_BYTES;
+  auto commit = [&](int st) {
+    if constexpr (!C::DIRECT) {
+      GENSOR_LDS char* abase = lds + st * C::STAGE_BYTES;
+      GENSOR_LDS char* bbase = abase + C::A_BYTES;
 #pragma unroll
-    for (int i = 0; i < C::A_LOADS; ++i) {
-      const int q = tid + i * C::THREADS;
-      if (C::A_CHUNKS % C::THREADS != 0 && q >= C::A_CHUNKS) break;
-      const int row = q / C::CPR, ch = q % C::CPR;
-      *(GENSOR_LDS u32x4*)(base + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16) = ra[i];
-    }
-  };
-  auto store_b = [&](int st) {
-    GENSOR_LDS char* base = lds + st * C::STAGE_BYTES + C::A_BYTES;
+      for (int i = 0; i < C::A_LOADS; ++i) {
+        const int q = tid + i * C::THREADS;
+        if (C::A_CHUNKS % C::THREADS != 0 && q >= C::A_CHUNKS) break;
+        *(GENSOR_LDS u32x4*)(abase + q * 16) = ra[i];
+      }
 #pragma unroll
-    for (int i = 0; i < C::B_LOADS; ++i) {
-      const int q = tid + i * C::THREADS;
-      if (C::B_CHUNKS % C::THREADS != 0 && q >= C::B_CHUNKS) break;
-      if constexpr (C::BSRC == B_KC) {
-        const int row = q / C::CPR, ch = q % C::CPR;
-        *(GENSOR_LDS u32x4*)(base + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16) = rb[i];
-      } else {
-        constexpr int CPRN = BN * ES / 16;
-        const int krow = q / CPRN, ch = q % CPRN;
-        *(GENSOR_LDS u32x4*)(base + krow * C::PITCH_N + ch * 16) = rb[i];
+      for (int i = 0; i < C::B_LOADS; ++i) {
+        const int q = tid + i * C::THREADS;
+        if (C::B_CHUNKS % C::THREADS != 0 && q >= C::B_CHUNKS) break;
+        if constexpr (C::BSRC == B_KC) {
+          *(GENSOR_LDS u32x4*)(bbase + q * 16) = rb[i];
+        } else {
+          constexpr int CPRN = BN * ES / 16;
+          *(GENSOR_LDS u32x4*)(bbase + (q / CPRN) * C::PITCH_N + (q % CPRN) * 16) = rb[i];
+        }
       }
     }
   };
-  // ---- global -> LDS directly (k-contiguous operands, vector path).  Each wave-level
-  // load deposits lane l's 16 bytes at (instruction base) + 16*l, so the swizzle is applied
-  // to the global address: the lane that owns LDS chunk slot (row, pc) fetches logical
-  // chunk pc ^ f(row).  Chunks outside the matrix are fetched from a clamped in-range
-  // address and the row/column they belong to is never stored, or contributes to k >= K
-  // only if K is not a multiple of BK, which the host rules out for this mode.
-  auto direct_tile = [&](const char* gbase, int64_t ld, int row0, int nrows_total, int k0, GENSOR_LDS char* dst, int chunks) {
-    for (int q0 = wave * 64; q0 < chunks; q0 += C::THREADS) {
-      const int q = q0 + lane;
-      const int row = q / C::CPR, pc = q % C::CPR;
-      const int ch = swizzled_chunk(row, pc, C::RPP, C::CPR);
-      int gr = row0 + row;
-      gr = gr < nrows_total ? gr : nrows_total - 1;
-      const char* src = gbase + ((int64_t)gr * ld + k0 + ch * EPC) * ES;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (GENSOR_LDS void*)(dst + q0 * 16), 16, 0, 0);
-    }
-  };
-  auto direct_load = [&](int k0, int st) {
-    GENSOR_LDS char* base = lds + st * C::STAGE_BYTES;
-    direct_tile(Ab, args.lda, m0, args.M, k0, base, C::A_CHUNKS);
-    direct_tile(Bb, args.ldb, n0, args.N, k0, base + C::A_BYTES, C::B_CHUNKS);
+  // all of this wave's direct deposits have landed (vmcnt(0); expcnt and lgkmcnt untouched)
+  auto wait_deposits = [&]() {
+    if constexpr (C::DIRECT) __builtin_amdgcn_s_waitcnt(0x0F70);
   };
 
-  // ---- fragment reads + MFMA for one LDS stage
+  // ---- fragments.  fa[b] / fb[b] are two register sets so that the reads of k step s+1
+  // are in flight while the MFMAs of step s issue.
   const int frow = lane % MB;          // row / column inside an MFMA block
   const int fgrp = lane / MB;          // which chunk of the k group this lane holds
   auto block_row = [&](int bi) {       // first row of MFMA block bi of this wave inside the BM tile
@@ -378,124 +426,175 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     constexpr int PER = C::NBLK / C::VN;
     return (bj / PER) * (BN / C::VN) + wave_n * (C::WN / C::VN) + (bj % PER) * MB;
   };
-  auto compute = [&](int st) {
+  u32x4 fa[2][C::MBLK], fb[2][C::NBLK];
+  auto read_frags = [&](int st, int ks, int buf) {
     GENSOR_LDS char* abase = lds + st * C::STAGE_BYTES;
     GENSOR_LDS char* bbase = abase + C::A_BYTES;
+    const int ch = ks * C::LANE_GROUPS + fgrp;
 #pragma unroll
-    for (int ks = 0; ks < C::KSTEPS; ++ks) {
-      u32x4 af[C::MBLK], bf[C::NBLK];
-      const int ch = ks * C::LANE_GROUPS + fgrp;
+    for (int bi = 0; bi < C::MBLK; ++bi) {
+      const int row = block_row(bi) + frow;
+      fa[buf][bi] = *(GENSOR_LDS u32x4*)(abase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16);
+    }
 #pragma unroll
-      for (int bi = 0; bi < C::MBLK; ++bi) {
-        const int row = block_row(bi) + frow;
-        af[bi] = *(GENSOR_LDS u32x4*)(abase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16);
+    for (int bj = 0; bj < C::NBLK; ++bj) {
+      if constexpr (C::BSRC == B_KC) {
+        const int row = block_col(bj) + frow;
+        fb[buf][bj] = *(GENSOR_LDS u32x4*)(bbase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16);
+      } else if constexpr (ES == 4) {
+        // fp32, [k][n] tile: element t of this lane's chunk is k = ks*KG + fgrp*4 + t
+        const int col = block_col(bj) + frow;
+        u32x4 v;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+          v[tt] = *(GENSOR_LDS uint32_t*)(bbase + (ks * C::KG + fgrp * 4 + tt) * C::PITCH_N + col * 4);
+        fb[buf][bj] = v;
+      } else {
+        // 16-bit, [k][n] tile: two transposing reads.  In each 16-lane group, lane s
+        // fetches 4 consecutive n of row (s/4) and receives, for column s, the 4
+        // consecutive k of the group's rows.
+        const int g = lane >> 4, s = lane & 15;
+        int krow, col;
+        if constexpr (MB == 32) {    // groups: (g%2) picks the 16-column half, (g/2) the 8-deep k half
+          krow = ks * C::KG + (g >> 1) * 8 + (s >> 2);
+          col = block_col(bj) + (g & 1) * 16 + (s & 3) * 4;
+        } else {                     // 16x16 blocks: group g holds k = 8g..8g+7
+          krow = ks * C::KG + g * 8 + (s >> 2);
+          col = block_col(bj) + (s & 3) * 4;
+        }
+        GENSOR_LDS char* p = bbase + krow * C::PITCH_N + col * 2;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)p);
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + 4 * C::PITCH_N));
+        u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+        u32x4 v = {l2[0], l2[1], h2[0], h2[1]};
+        fb[buf][bj] = v;
+      }
+    }
+  };
+  auto mma = [&](int buf) {
+#pragma unroll
+    for (int bi = 0; bi < C::MBLK; ++bi)
+#pragma unroll
+      for (int bj = 0; bj < C::NBLK; ++bj) MF::run(fa[buf][bi], fb[buf][bj], acc[bi][bj]);
+  };
+
+  // ---- main loop over k tiles.  Tile kt+1 is fetched while tile kt is multiplied; its
+  // first fragments are read right after the barrier, under the MFMAs of the last k step
+  // of tile kt, so that the barrier and the LDS latency are covered by matrix work.
+  const int nk = (args.K + BK - 1) / BK;
+  constexpr bool PIPE = (C::KSTEPS % 2 == 0) && C::STAGES == 2;
+  fetch_a(0, 0);
+  fetch_b(0, 0);
+  commit(0);
+  wait_deposits();
+  __syncthreads();
+  if constexpr (PIPE) {
+    read_frags(0, 0, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+      const bool more = kt + 1 < nk;
+      const int cur = kt & 1, nxt = cur ^ 1;
+      if (more) {
+        fetch_a((kt + 1) * BK, nxt);
+        fetch_b((kt + 1) * BK, nxt);
       }
 #pragma unroll
-      for (int bj = 0; bj < C::NBLK; ++bj) {
-        if constexpr (C::BSRC == B_KC) {
-          const int row = block_col(bj) + frow;
-          bf[bj] = *(GENSOR_LDS u32x4*)(bbase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16);
-        } else if constexpr (ES == 4) {
-          // fp32, [k][n] tile: element t of this lane's chunk is k = ks*KG + fgrp*4 + t
-          const int col = block_col(bj) + frow;
-          u32x4 v;
-#pragma unroll
-          for (int tt = 0; tt < 4; ++tt)
-            v[tt] = *(GENSOR_LDS uint32_t*)(bbase + (ks * C::KG + fgrp * 4 + tt) * C::PITCH_N + col * 4);
-          bf[bj] = v;
-        } else {
-          // 16-bit, [k][n] tile: two transposing reads.  In each 16-lane group, lane s
-          // fetches 4 consecutive n of row (s/4) and receives, for column s, the 4
-          // consecutive k of the group's rows.
-          const int g = lane >> 4, s = lane & 15;
-          int krow, col;
-          if constexpr (MB == 32) {    // groups: (g%2) picks the 16-column half, (g/2) the 8-deep k half
-            krow = ks * C::KG + (g >> 1) * 8 + (s >> 2);
-            col = block_col(bj) + (g & 1) * 16 + (s & 3) * 4;
-          } else {                     // 16x16 blocks: group g holds k = 8g..8g+7
-            krow = ks * C::KG + g * 8 + (s >> 2);
-            col = block_col(bj) + (s & 3) * 4;
-          }
-          GENSOR_LDS char* p = bbase + krow * C::PITCH_N + col * 2;
-          s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)p);
-          s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + 4 * C::PITCH_N));
-          u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-          u32x4 v = {l2[0], l2[1], h2[0], h2[1]};
-          bf[bj] = v;
+      for (int ks = 0; ks < C::KSTEPS; ++ks) {
+        if (ks + 1 < C::KSTEPS) {
+          read_frags(cur, ks + 1, (ks + 1) & 1);
+        } else if (more) {
+          commit(nxt);
+          wait_deposits();
+          __syncthreads();
+          read_frags(nxt, 0, 0);
+        }
+        mma(ks & 1);
+      }
+    }
+  } else {
+    for (int kt = 0; kt < nk; ++kt) {
+      const bool more = kt + 1 < nk;
+      const int cur = C::STAGES == 2 ? (kt & 1) : 0, nxt = C::STAGES == 2 ? (cur ^ 1) : 0;
+      if (more) {
+        if constexpr (!C::DIRECT || C::STAGES == 2) {
+          fetch_a((kt + 1) * BK, nxt);
+          fetch_b((kt + 1) * BK, nxt);
         }
       }
 #pragma unroll
-      for (int bi = 0; bi < C::MBLK; ++bi)
-#pragma unroll
-        for (int bj = 0; bj < C::NBLK; ++bj) MF::run(af[bi], bf[bj], acc[bi][bj]);
-    }
-  };
-
-  // ---- main loop over k tiles
-  const int nk = (args.K + BK - 1) / BK;
-  if constexpr (C::DIRECT) {
-    direct_load(0, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-      __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's deposits have landed
-      __syncthreads();                           // everyone's deposits visible; previous compute finished
-      if (kt + 1 < nk) direct_load((kt + 1) * BK, (kt + 1) % C::STAGES);
-      compute(kt % C::STAGES);
-      if constexpr (C::STAGES == 1) __syncthreads();
-    }
-  } else {
-    load_a(0);
-    load_b(0);
-    store_a(0);
-    store_b(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      const bool more = kt + 1 < nk;
-      if (more) {
-        load_a((kt + 1) * BK);
-        load_b((kt + 1) * BK);
+      for (int ks = 0; ks < C::KSTEPS; ++ks) {
+        read_frags(cur, ks, 0);
+        mma(0);
       }
-      compute(kt % C::STAGES);
-      if constexpr (C::STAGES == 1) __syncthreads();
-      if (more) {
-        store_a((kt + 1) % C::STAGES);
-        store_b((kt + 1) % C::STAGES);
+      if constexpr (C::STAGES == 1) {
+        __syncthreads();                       // everyone is done reading the single buffer
+        if constexpr (C::DIRECT) {
+          if (more) {
+            fetch_a((kt + 1) * BK, 0);
+            fetch_b((kt + 1) * BK, 0);
+          }
+        }
       }
+      if (more) commit(nxt);
+      wait_deposits();
       __syncthreads();
     }
   }
 
-  // ---- epilogue: C = alpha * acc + beta * C.  In a 32x32 block lane l holds column l%32
-  // of rows 8*(v/4) + 4*(l/32) + v%4; in a 16x16 block column l%16 of rows 4*(l/16) + v.
+  // ---- epilogue: C = alpha * acc + beta * C through a buffer descriptor that starts at this
+  // tile's first element; rows and columns outside the matrix are sent out of range.  In a
+  // 32x32 block lane l holds column l%32 of rows 8*(v/4) + 4*(l/32) + v%4; in a 16x16 block
+  // column l%16 of rows 4*(l/16) + v.
   typedef typename C::OutT OutT;
-  char* Cb = (char*)args.C + (int64_t)bidx * args.strideC * ElemSize<OutT>::value;
+  constexpr int OS = ElemSize<OutT>::value;
+  char* Cb = (char*)args.C + (int64_t)bidx * args.strideC * OS;
   const float alpha = args.alpha, beta = args.beta;
+  if constexpr (C::BSRC == B_CONV) {
+    // output O[img][filter][p][q]: row = filter, col = (img, p, q)
+    const int pq = args.cP * args.cQ;
 #pragma unroll
-  for (int bi = 0; bi < C::MBLK; ++bi)
+    for (int bi = 0; bi < C::MBLK; ++bi)
 #pragma unroll
-    for (int bj = 0; bj < C::NBLK; ++bj) {
-      const int col = n0 + block_col(bj) + frow;
+      for (int bj = 0; bj < C::NBLK; ++bj) {
+        const int col = n0 + block_col(bj) + frow;
+        const int img = col / pq;
+        const int64_t cbase = (int64_t)img * args.M * pq + (col - img * pq);
 #pragma unroll
-      for (int v = 0; v < MF::NACC; ++v) {
-        int r;
-        if constexpr (MB == 32) r = 8 * (v / 4) + 4 * fgrp + (v % 4);
-        else r = 4 * fgrp + v;
-        const int row = m0 + block_row(bi) + r;
-        if (row < args.M && col < args.N) {
-          int64_t idx;
-          if constexpr (C::BSRC == B_CONV) {
-            // output O[img][filter][p][q]: row = filter, col = (img, p, q)
-            const int pq = args.cP * args.cQ;
-            const int img = col / pq;
-            idx = ((int64_t)img * args.M + row) * pq + (col - img * pq);
-          } else {
-            idx = (int64_t)row * args.ldc + col;
-          }
-          float val = alpha * acc[bi][bj][v];
-          if (beta != 0.f) val += beta * to_float<OutT>(Cb, idx);
-          store_out<OutT>(Cb, idx, val);
+        for (int v = 0; v < MF::NACC; ++v) {
+          const int r = (MB == 32) ? 8 * (v / 4) + 4 * fgrp + (v % 4) : 4 * fgrp + v;
+          const int row = m0 + block_row(bi) + r;
+          if (row < args.M && col < args.N) store_out<OutT>(Cb, cbase + (int64_t)row * pq, alpha * acc[bi][bj][v]);
         }
       }
-    }
+  } else {
+    const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(Cb + ((int64_t)m0 * args.ldc + n0) * OS), 0,
+        clamp_records(((int64_t)(rows_valid - 1) * args.ldc + cols_valid) * OS), RSRC_FLAGS);
+#pragma unroll
+    for (int bi = 0; bi < C::MBLK; ++bi)
+#pragma unroll
+      for (int bj = 0; bj < C::NBLK; ++bj) {
+        const int col = block_col(bj) + frow;
+#pragma unroll
+        for (int v = 0; v < MF::NACC; ++v) {
+          const int r = (MB == 32) ? 8 * (v / 4) + 4 * fgrp + (v % 4) : 4 * fgrp + v;
+          const int row = block_row(bi) + r;
+          const uint32_t off = (col < cols_valid) ? (uint32_t)((row * (int)args.ldc + col) * OS) : OOB;
+          float val = alpha * acc[bi][bj][v];
+          if constexpr (OS == 4) {
+            if (beta != 0.f) val += beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, off, 0, 0));
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), rc, off, 0, 0);
+          } else {
+            if (beta != 0.f) {
+              const uint16_t old = __builtin_amdgcn_raw_buffer_load_b16(rc, off, 0, 0);
+              val += beta * to_float<OutT>(&old, 0);
+            }
+            uint16_t bits;
+            store_out<OutT>(&bits, 0, val);
+            __builtin_amdgcn_raw_buffer_store_b16(bits, rc, off, 0, 0);
+          }
+        }
+      }
+  }
 }
 
 }  // namespace gensor

@@ -166,6 +166,11 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
   if (d->vec && !vec_ok) return GENSOR_ERR_NO_SCHEDULE;          // schedule asks for vector accesses the operands cannot give
   if (d->direct && v.K % d->bk != 0) return GENSOR_ERR_NO_SCHEDULE;
   if (s->split_k > 1) return GENSOR_ERR_UNSUPPORTED;
+  // 32-bit offsets inside one workgroup tile
+  const int64_t lim = 0x7fffffffll;
+  if ((int64_t)(d->bm + 1) * lda * v.esize >= lim || (int64_t)(d->bm + 1) * ldc * v.osize >= lim) return GENSOR_ERR_UNSUPPORTED;
+  if (v.bsrc == B_KC && (int64_t)(d->bn + 1) * ldb * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
+  if (v.bsrc == B_NC && ((int64_t)(d->bk + 1) * ldb + d->bn) * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
 
   KernelArgs a;
   std::memset(&a, 0, sizeof(a));

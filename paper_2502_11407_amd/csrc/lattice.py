@@ -28,6 +28,15 @@ def lattice():
         (64, 64, 64, 32, 32, 32, 1, 1),
         (64, 64, 64, 32, 32, 16, 1, 1),
         (32, 32, 64, 16, 16, 16, 1, 1),
+        # eight waves per workgroup (two per SIMD)
+        (256, 256, 64, 128, 64, 32, 1, 1),
+        (256, 256, 64, 64, 128, 32, 1, 1),
+        (256, 128, 64, 64, 64, 32, 1, 1),
+        (128, 256, 64, 64, 64, 32, 1, 1),
+        # other k depths
+        (256, 256, 32, 128, 128, 32, 1, 1),
+        (128, 128, 32, 64, 64, 32, 1, 1),
+        (128, 128, 128, 64, 64, 32, 1, 1),
     ]
     for dt in ("f16", "bf16"):
         for bsrc in ("KC", "NC", "CONV"):
@@ -36,8 +45,9 @@ def lattice():
             # scalar-access instance: any alignment, any extents
             out.append(_inst(dt, "f32", 64, 64, 32, 32, 32, 16, 1, 1, bsrc, vec=0))
         # direct global->LDS staging for k-contiguous operands
-        out.append(_inst(dt, "f32", 256, 256, 64, 128, 128, 32, 1, 1, "KC", direct=1))
-        out.append(_inst(dt, "f32", 128, 128, 64, 64, 64, 32, 1, 1, "KC", direct=1))
+        for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles16:
+            if bm * bn >= 128 * 128:
+                out.append(_inst(dt, "f32", bm, bn, bk, wm, wn, mb, vm, vn, "KC", direct=1))
         # 16-bit output variants
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "KC"))
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "NC"))
