@@ -125,6 +125,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--only-headline", action="store_true", help="skip the other operator shapes and the CPU legs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 256 MiB device copy, the known-size reference for HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (single-GPU operators, "
@@ -136,6 +138,13 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     from paper_2502_11407_amd import binding as gs, inputs
+
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")     # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     w = inputs.config2_gemm_f16()
     head = Case(gs, inputs, w)

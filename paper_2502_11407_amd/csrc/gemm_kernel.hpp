@@ -189,7 +189,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int wave_m = wave / C::WAVES_N;
   const int wave_n = wave % C::WAVES_N;
 
@@ -478,6 +478,20 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       for (int bj = 0; bj < C::NBLK; ++bj) MF::run(fa[buf][bi], fb[buf][bj], acc[bi][bj]);
   };
 
+  // Scheduling hint for one k step: issue the fragment reads of the next step in small
+  // groups in front of each MFMA of this step, so that they complete under matrix work.
+  auto interleave = [&]() {
+    constexpr int NM = C::MBLK * C::NBLK * (ES == 4 ? 4 : 1);
+    constexpr int NR = C::MBLK + C::NBLK * (C::BSRC == B_KC ? 1 : (ES == 4 ? 4 : 2));
+    constexpr int RPM = (NR + NM - 1) / NM;
+#pragma unroll
+    for (int i = 0; i < NM; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);   // LDS reads
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
   // ---- main loop over k tiles.  Tile kt+1 is fetched while tile kt is multiplied; its
   // first fragments are read right after the barrier, under the MFMAs of the last k step
   // of tile kt, so that the barrier and the LDS latency are covered by matrix work.
@@ -508,6 +522,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
           read_frags(nxt, 0, 0);
         }
         mma(ks & 1);
+        interleave();
       }
     }
   } else {
