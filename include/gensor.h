@@ -115,9 +115,9 @@ const gensor_hw* gensor_hw_mi355x(void);
 /* Walk parameters (inputs "T, threshold" of Algorithm 1 plus this build's knobs).
  * Zero in any field selects its default. */
 typedef struct {
-  double T0;                  /* initial temperature, default 1.0 */
-  double threshold;           /* stop when T <= threshold, default 2^-100 (100 steps, Section IV-D) */
-  int32_t chains;             /* independent seeded walks, default 256 */
+  double T0;                  /* initial (and per-level restart) temperature, default 2^30 */
+  double threshold;           /* stop when T <= threshold, default 2^-70 (100 steps, Section IV-D) */
+  int32_t chains;             /* independent seeded walks, default 1024 */
   int32_t keep_policy;        /* 0: keep every complete state; 1: the paper's printed keep probability */
   int32_t tiling_benefit;     /* 0: Eq. 1 as printed; 1: footprint ratio inverted (ablation) */
   int32_t no_vthread;         /* 1: setVThread disabled (ablation) */

@@ -48,8 +48,10 @@ Readings (the paper is silent or garbled here)
              workgroup fits the wave limit is a complete program (stop there), so policy 0
              keeps each such visited state in its completed form; policy 1 keeps it with
              the printed probability 1 - 1/(1 + exp(-0.5 (-ln T - 10)))
-  pick       kept complete states are ranked by the analytical cost model below; the best one
-             that exists as a compiled instance wins (else the nearest instance to the best)
+  pick       kept complete states are ranked by the analytical cost model below.  A state is
+             realised by the compiled instances on the same six tile sizes whose V is nearest to
+             its own; the best such instance over all kept states wins (if none exists, the
+             instance nearest to the best-ranked state)
 """
 from __future__ import annotations
 
@@ -108,7 +110,7 @@ class Hw:
 class Opts:
     T0: float = 2.0 ** 30
     threshold: float = 2.0 ** -70
-    chains: int = 256
+    chains: int = 1024
     keep_policy: int = 0
     tiling_benefit: int = 0
     no_vthread: int = 0
@@ -416,7 +418,8 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     t_cu = cu_tiles * (t_main + t_epi / resident) + t_fill
     bytes_total = view.batch * (e * (view.M * view.K + view.K * view.N) + eo * view.M * view.N)
     t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3)
-    return max(t_cu, t_hbm) + hw.launch_us
+    # soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)
+    return max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + hw.launch_us
 
 
 def pick(view: View, hw: Hw, kept: Sequence[State], instances: Sequence[Instance], vec_ok: bool) -> Tuple[Optional[Instance], float, int]:
@@ -432,10 +435,13 @@ def pick(view: View, hw: Hw, kept: Sequence[State], instances: Sequence[Instance
         bm, bn, bk = s.tile[0][0], s.tile[1][0], s.tile[2][0]
         wm, wn, kg = s.tile[0][1], s.tile[1][1], s.tile[2][1]
         scored += 1
-        exact = [i for i in instances if (i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn) ==
-                 (bm, bn, bk, wm, wn, kg, s.v[0], s.v[1]) and (vec_ok or not i.vec)
-                 and (not i.direct or view.K % i.bk == 0)]
-        for i in exact:
+        # instances on the same tiles; among them those whose V is nearest to the state's
+        same = [i for i in instances if (i.bm, i.bn, i.bk, i.wm, i.wn, i.kg) == (bm, bn, bk, wm, wn, kg)
+                and (vec_ok or not i.vec) and (not i.direct or view.K % i.bk == 0)]
+        vdist = [abs(math.log2(i.vm) - math.log2(s.v[0])) + abs(math.log2(i.vn) - math.log2(s.v[1])) for i in same]
+        for i, dv in zip(same, vdist):
+            if dv != min(vdist):
+                continue
             us = predict_us(view, hw, i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn, i.vec, i.stages, i.direct)
             if us > 0 and (best is None or us < best_us):
                 best, best_us = i, us

@@ -78,7 +78,7 @@ int next_pow2(int64_t x) {
 void make_ctx(const GemmView& v, const gensor_hw* hw, const gensor_construct_opts* o, Ctx* c) {
   c->view = v;
   c->hw = hw ? *hw : kMi355x;
-  gensor_construct_opts d = {std::ldexp(1.0, 30), std::ldexp(1.0, -70), 256, 0, 0, 0};
+  gensor_construct_opts d = {std::ldexp(1.0, 30), std::ldexp(1.0, -70), 1024, 0, 0, 0};
   if (o) {
     if (o->T0 > 0) d.T0 = o->T0;
     if (o->threshold > 0) d.threshold = o->threshold;
@@ -309,7 +309,8 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   const double t_cu = cu_tiles * (t_main + t_epi / resident) + t_fill;
   const double bytes_total = (double)v.batch * ((double)e * ((double)v.M * v.K + (double)v.K * v.N) + (double)eo * v.M * v.N);
   const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3);
-  return (t_cu > t_hbm ? t_cu : t_hbm) + hw.launch_us;
+  // soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)
+  return (t_cu > t_hbm ? t_cu : t_hbm) + 0.3 * (t_cu > t_hbm ? t_hbm : t_cu) + hw.launch_us;
 }
 
 double predict_instance(const GemmView& v, const gensor_hw& hw, const InstanceDesc& d) {
@@ -351,12 +352,21 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
   for (const Etir& e : kept) {
     if (!seen.insert(e).second) continue;
     ++scored;
+    // instances on the same tiles; among them those whose V is nearest to the state's
+    auto same_tiles = [&](const InstanceDesc& d) {
+      return d.bm == e.tile[0][0] && d.bn == e.tile[1][0] && d.bk == e.tile[2][0] && d.wm == e.tile[0][1] &&
+             d.wn == e.tile[1][1] && d.kg == e.tile[2][1] && usable(d, v, vec_ok);
+    };
+    auto vdist = [&](const InstanceDesc& d) {
+      return std::fabs(std::log2((double)d.vm) - std::log2((double)e.v[0])) +
+             std::fabs(std::log2((double)d.vn) - std::log2((double)e.v[1]));
+    };
+    double vmin = -1.0;
+    for (int i = 0; i < g_num_instances; ++i)
+      if (same_tiles(g_instances[i]) && (vmin < 0 || vdist(g_instances[i]) < vmin)) vmin = vdist(g_instances[i]);
     for (int i = 0; i < g_num_instances; ++i) {
       const InstanceDesc& d = g_instances[i];
-      if (d.bm != e.tile[0][0] || d.bn != e.tile[1][0] || d.bk != e.tile[2][0] || d.wm != e.tile[0][1] ||
-          d.wn != e.tile[1][1] || d.kg != e.tile[2][1] || d.vm != e.v[0] || d.vn != e.v[1])
-        continue;
-      if (!usable(d, v, vec_ok)) continue;
+      if (!same_tiles(d) || vdist(d) != vmin) continue;
       const double us = predict_instance(v, c.hw, d);
       if (us > 0 && (!best || us < best_us)) { best = &d; best_us = us; }
     }
