@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "f32": 157.3}   # dense MFMA, MI355X
 HBM_GBS = 8000.0
+# HBM bytes per launch of the headline kernel from the FETCH_SIZE / WRITE_SIZE counter passes (each scaled by
+# the same counter's reading for a 256 MiB device copy); keyed by (tile, wave tile, direct) of the instance
+# they were measured on.  Any other instance reports null.
+MEASURED_TRAFFIC_BYTES = {((256, 256, 64), (128, 64), 1): 268.6e6, ((256, 256, 64), (64, 128), 1): 268.6e6}
 
 
 def _algorithmic_bytes(w, gs_inputs):
@@ -151,6 +155,9 @@ def main():
     ms, wall_ms = head.time_ms(args.steps, args.warmup)
     tflops = w.flops / (ms * 1e-3) / 1e12
     peak = PEAK_TFLOPS[w.dtype]
+    sd = head.sched.describe()
+    traffic = MEASURED_TRAFFIC_BYTES.get(((sd["tile_m"][0], sd["tile_n"][0], sd["tile_k"][0]),
+                                          (sd["tile_m"][1], sd["tile_n"][1]), sd["direct_lds"]))
     line = {
         "metric": "TFLOP/s and % of MFMA peak per operator on 1 MI355X; construction time (s)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -163,7 +170,7 @@ def main():
         "construct_s": head.construct_s,
         "wall_ms_per_step": wall_ms,
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": peak, "unit": "TFLOP/s",
-                     "frac": tflops / peak, "traffic": None},
+                     "frac": tflops / peak, "traffic": traffic},
     }
     if not args.only_headline:
         line["parity_rel_frobenius_sampled"] = head.parity()
