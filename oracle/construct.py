@@ -405,7 +405,7 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     lds_bw = hw.bandwidth_gbs[1] * 1e3 / hw.compute_units                                     # bytes/us per CU
     t_lds = e * kp * (bm * (bn // wn) + bn * (bm // wm) + (bm + bn)) / lds_bw
     l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units
-    gather = 4.0 if view.bsrc == 2 else 1.0
+    gather = 4.0 if (view.bsrc == 2 and not direct) else 1.0
     scalar = 1.0 if vec else 6.0
     t_feed = scalar * e * kp * (bm + gather * bn) / l2_bw
     overlap = 0.55 + 0.1 * min(resident * nwaves / hw.simds_per_cu, 3.0)
@@ -437,7 +437,7 @@ def pick(view: View, hw: Hw, kept: Sequence[State], instances: Sequence[Instance
         scored += 1
         # instances on the same tiles; among them those whose V is nearest to the state's
         same = [i for i in instances if (i.bm, i.bn, i.bk, i.wm, i.wn, i.kg) == (bm, bn, bk, wm, wn, kg)
-                and (vec_ok or not i.vec) and (not i.direct or view.K % i.bk == 0)]
+                and (vec_ok or not i.vec) and (not i.direct or view.bsrc == 2 or view.K % i.bk == 0)]
         vdist = [abs(math.log2(i.vm) - math.log2(s.v[0])) + abs(math.log2(i.vn) - math.log2(s.v[1])) for i in same]
         for i, dv in zip(same, vdist):
             if dv != min(vdist):
@@ -453,7 +453,7 @@ def pick(view: View, hw: Hw, kept: Sequence[State], instances: Sequence[Instance
         target = [s.tile[0][0], s.tile[1][0], s.tile[2][0], s.tile[0][1], s.tile[1][1], s.tile[2][1], s.v[0], s.v[1]]
         bd = None
         for i in instances:
-            if (i.vec and not vec_ok) or (i.direct and view.K % i.bk != 0):
+            if (i.vec and not vec_ok) or (i.direct and view.bsrc != 2 and view.K % i.bk != 0):
                 continue
             us = predict_us(view, hw, i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn, i.vec, i.stages, i.direct)
             if us <= 0:

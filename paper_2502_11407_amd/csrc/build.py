@@ -35,8 +35,8 @@ def generate():
         src = ['#include "registry.hpp"', "namespace gensor {"]
         for d in group:
             src.append("typedef %s C_%d;" % (lattice.cfg_type(d), d["id"]))
-            src.append("hipError_t launch_%d(const KernelArgs& a, hipStream_t st) { return launch_instance<C_%d>(a, st); }"
-                       % (d["id"], d["id"]))
+            src.append("hipError_t launch_%d(const KernelArgs& a, hipStream_t st) { return %s<C_%d>(a, st); }"
+                       % (d["id"], "launch_conv_instance" if d["units"] else "launch_instance", d["id"]))
         src.append("}  // namespace gensor\n")
         path = os.path.join(GEN, "inst_%03d.hip" % (t // PER_TU))
         _write_if_changed(path, "\n".join(src))
@@ -50,11 +50,11 @@ def generate():
         kg = (64 // d["mb"]) * (16 // es)
         a_bytes = d["bm"] * d["bk"] * es
         b_bytes = d["bn"] * d["bk"] * es if d["bsrc"] == "KC" else d["bk"] * (d["bn"] * es + 32)
-        lds = (a_bytes + b_bytes) * d["stages"]
+        lds = 0 if d["units"] else (a_bytes + b_bytes) * d["stages"]
         threads = (d["bm"] // d["wm"]) * (d["bn"] // d["wn"]) * 64
-        reg.append("  {%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, launch_%d}," % (
+        reg.append("  {%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, launch_%d}," % (
             d["id"], lattice.DT[d["dt"]], lattice.DT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"],
-            d["vm"], d["vn"], lattice.BSRC[d["bsrc"]], d["vec"], d["stages"], d["direct"], lds, threads, kg, d["id"]))
+            d["vm"], d["vn"], lattice.BSRC[d["bsrc"]], d["vec"], d["stages"], d["direct"], lds, threads, kg, d["units"], d["id"]))
     reg.append("};")
     reg.append("const int g_num_instances = %d;" % len(L))
     reg.append("}  // namespace gensor")
@@ -67,7 +67,7 @@ def generate():
 
 def _compile(src):
     obj = os.path.join(GEN, os.path.basename(src).rsplit(".", 1)[0] + ".o")
-    deps = [src, os.path.join(HERE, "gemm_kernel.hpp"), os.path.join(HERE, "registry.hpp"),
+    deps = [src, os.path.join(HERE, "gemm_kernel.hpp"), os.path.join(HERE, "conv_kernel.hpp"), os.path.join(HERE, "registry.hpp"),
             os.path.join(HERE, "host_common.hpp"), os.path.join(PKG, "..", "include", "gensor.h")]
     if os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps if os.path.exists(d)):
         return obj

@@ -1,0 +1,310 @@
+// Convolution as an implicit GEMM with the input patch cached in LDS (the "cache" primitive
+// applied to the halo tile): O = (I * K) downsampled by S on NCHW input and KCRS filters,
+// cross-correlation with zero padding (operator table, Conv2d row).
+//
+// GEMM view: m = filter, n = (image, out row, out col), k = (filter row, filter col, channel)
+// with the channel innermost.  One LDS stage holds BKC channels:
+//   * the filters of this workgroup's BM rows, permuted on the way in from (c, r, s) to
+//     (r, s, c) order, as a k-contiguous tile [BM][R*S*BKC] (row pitch an odd number of
+//     16-byte chunks, so 16 consecutive rows fall in 16 different bank groups);
+//   * the input patch that the workgroup's BN output pixels touch, channel-last:
+//     [patch row][patch col][BKC channels + 16 bytes pad].  A patch row is a row of the
+//     zero-padded images stacked on top of each other; rows and columns outside an image are
+//     never written and stay zero.  Global reads run along x (16 bytes per channel), an
+//     8x8 (4x4 for fp32) register transpose turns them into channel-contiguous 16-byte
+//     LDS writes, so every input element is fetched once per workgroup, not once per tap.
+// A lane's B fragment for tap (r, s) and channel chunk c is then ONE aligned 16-byte LDS
+// read at  lane_base + (r*PW + s)*SLOT + c*16 : the tap is a scalar offset, there is no
+// per-tap address arithmetic and no im2col buffer.
+#pragma once
+#include "gemm_kernel.hpp"
+
+namespace gensor {
+
+template <typename T_, typename OutT_, int BM_, int BN_, int BKC_, int WM_, int WN_, int MB_, int UNITS_>
+struct ConvCfg {
+  typedef T_ T;
+  typedef OutT_ OutT;
+  static constexpr int BM = BM_, BN = BN_, BKC = BKC_, WM = WM_, WN = WN_, MB = MB_;
+  static constexpr int ES = ElemSize<T>::value;
+  static constexpr int EPC = 16 / ES;
+  static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, WAVES = WAVES_M * WAVES_N;
+  static constexpr int THREADS = WAVES * 64;
+  static constexpr int MBLK = WM / MB, NBLK = WN / MB;
+  static constexpr int LANE_GROUPS = 64 / MB;
+  static constexpr int KG = LANE_GROUPS * EPC;
+  static constexpr int KSTEPS_C = BKC / KG;            // MFMA k steps per tap
+  static constexpr int OCT = BKC / EPC;                // 16-byte channel groups per pixel
+  static constexpr int SLOT = BKC * ES + 16;           // bytes per patch pixel
+  static constexpr int RS_MAX = 9;                     // taps supported by the staging registers
+  static constexpr int A_VEC_MAX = (BM * BKC * RS_MAX / EPC + THREADS - 1) / THREADS;
+  static constexpr int UNITS_MAX = UNITS_;             // patch transpose units per thread and stage
+  static_assert(BKC % KG == 0 && KSTEPS_C >= 1, "channel tile must hold whole fragment k groups");
+  static_assert(BM % WM == 0 && BN % WN == 0 && WM % MB == 0 && WN % MB == 0, "tiles");
+};
+
+template <typename C>
+__global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs args) {
+  typedef typename C::T T;
+  typedef Mfma<T, C::MB> MF;
+  typedef typename MF::Acc Acc;
+  constexpr int ES = C::ES, EPC = C::EPC, BM = C::BM, BN = C::BN, BKC = C::BKC, MB = C::MB, SLOT = C::SLOT;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  GENSOR_LDS char* lds = (GENSOR_LDS char*)smem;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_m = wave / C::WAVES_N;
+  const int wave_n = wave % C::WAVES_N;
+
+  // workgroup -> (filter tile, pixel tile): contiguous tile ranges per XCD, panels of tile rows
+  const int total = args.tiles_m * args.tiles_n;
+  int wg = blockIdx.x;
+  if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
+  int tile_m, tile_n;
+  {
+    const int panel = args.panel;
+    const int per_panel = panel * args.tiles_n;
+    const int pi = wg / per_panel;
+    const int rows_here = min(panel, args.tiles_m - pi * panel);
+    const int r = wg - pi * per_panel;
+    tile_m = pi * panel + r % rows_here;
+    tile_n = r / rows_here;
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  // geometry
+  const int Cc = args.cC, H = args.cH, W = args.cW, R = args.cR, S = args.cS, P = args.cP, Q = args.cQ;
+  const int stride = args.cStride, pad = args.cPad, NI = args.cN;
+  const int RS = R * S, PQ = P * Q;
+  const int Hp = H + 2 * pad, PW = W + 2 * pad;
+  const int HW = H * W;
+  const int a_pitch = args.cApitch;            // bytes per filter row in LDS
+  const int patch_rows = args.cPatchRows;
+  const int stage_bytes = args.cStageBytes;
+  const int a_bytes = BM * a_pitch;
+  const int g_first = n0 / Q;                  // first stacked output row of this tile
+  const int R0 = (g_first / P) * Hp + (g_first % P) * stride;   // first stacked padded input row
+
+  constexpr uint32_t RSRC_FLAGS = 0x00020000u, OOB = 0x80000000u;
+  const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void*)args.B, 0, (uint32_t)args.cInBytes, RSRC_FLAGS);
+  const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)args.A, 0, (uint32_t)args.cWBytes, RSRC_FLAGS);
+
+  Acc acc[C::MBLK][C::NBLK];
+#pragma unroll
+  for (int i = 0; i < C::MBLK; ++i)
+#pragma unroll
+    for (int j = 0; j < C::NBLK; ++j)
+#pragma unroll
+      for (int v = 0; v < MF::NACC; ++v) acc[i][j][v] = 0.f;
+
+  // ---- filter staging plan.  Vector v of this thread covers EPC consecutive stored
+  // elements (c, r, s order) of filter row a_row[v], starting at local element a_e0[v];
+  // element e goes to k' = (e % RS) * BKC + e / RS.
+  const int a_vec_per_row = BKC * RS / EPC;
+  const int a_vecs = BM * a_vec_per_row;
+  int a_goff[C::A_VEC_MAX];        // element offset of the vector inside the filter tensor at channel tile 0
+  int a_dst[C::A_VEC_MAX];         // LDS byte offset of filter row + packed (rs, c) of the first element
+  u32x4 a_reg[C::A_VEC_MAX];
+#pragma unroll
+  for (int v = 0; v < C::A_VEC_MAX; ++v) {
+    const int q = tid + v * C::THREADS;
+    const int row = q / a_vec_per_row, e0 = (q - row * a_vec_per_row) * EPC;
+    const int c_lo = e0 / RS, rs0 = e0 - c_lo * RS;
+    const bool ok = q < a_vecs && (m0 + row) < args.M;
+    a_goff[v] = ok ? ((m0 + row) * Cc) * RS + e0 : -1;
+    a_dst[v] = (row * a_pitch) | (rs0 << 20) | (c_lo << 24);       // a_pitch * BM < 2^20
+  }
+  auto fetch_a = [&](int c0) {
+#pragma unroll
+    for (int v = 0; v < C::A_VEC_MAX; ++v) {
+      // channels at or beyond C: the whole vector may straddle, so validity is per element below
+      const uint32_t off = a_goff[v] >= 0 ? (uint32_t)((a_goff[v] + c0 * RS) * ES) : OOB;
+      a_reg[v] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, off, 0, 0);
+    }
+  };
+  auto commit_a = [&](int st, int c0) {
+    GENSOR_LDS char* base = lds + st * stage_bytes;
+#pragma unroll
+    for (int v = 0; v < C::A_VEC_MAX; ++v) {
+      if (tid + v * C::THREADS >= a_vecs) break;
+      const int rowoff = a_dst[v] & 0xfffff;
+      int rs = (a_dst[v] >> 20) & 15, cl = a_dst[v] >> 24;
+#pragma unroll
+      for (int i = 0; i < EPC; ++i) {
+        uint32_t bits;
+        if constexpr (ES == 4) bits = a_reg[v][i];
+        else bits = (a_reg[v][i >> 1] >> ((i & 1) * 16)) & 0xffffu;
+        if (c0 + cl >= Cc) bits = 0u;                                 // channel tail of the last stage
+        GENSOR_LDS char* p = base + rowoff + (rs * BKC + cl) * ES;
+        if constexpr (ES == 4) *(GENSOR_LDS uint32_t*)p = bits;
+        else *(GENSOR_LDS uint16_t*)p = (uint16_t)bits;
+        if (++rs == RS) { rs = 0; ++cl; }
+      }
+    }
+  };
+
+  // ---- patch staging plan.  A unit is EPC channels x EPC consecutive x of one patch row.
+  const int w_segs = (W + EPC - 1) / EPC;
+  const int units = patch_rows * w_segs * C::OCT;
+  int u_goff[C::UNITS_MAX];        // element offset of (img, channel group, y, x segment) at channel tile 0, or -1
+  int u_dst[C::UNITS_MAX];         // LDS byte offset of the unit's first pixel and channel group
+  int u_nx[C::UNITS_MAX];          // valid x in the segment
+  u32x4 u_reg[C::UNITS_MAX][C::EPC];
+#pragma unroll
+  for (int u = 0; u < C::UNITS_MAX; ++u) {
+    const int q = tid + u * C::THREADS;
+    const int oct = q % C::OCT, t = q / C::OCT;
+    const int seg = t % w_segs, j = t / w_segs;
+    const int srow = R0 + j;                       // stacked padded row
+    const int img = srow / Hp, y = srow - img * Hp - pad;
+    const bool ok = q < units && img < NI && y >= 0 && y < H;
+    u_goff[u] = ok ? ((img * Cc + oct * EPC) * H + y) * W + seg * EPC : -1;
+    u_dst[u] = (j * PW + pad + seg * EPC) * SLOT + oct * 16;
+    u_nx[u] = min(EPC, W - seg * EPC);
+  }
+  auto fetch_patch = [&](int c0) {
+#pragma unroll
+    for (int u = 0; u < C::UNITS_MAX; ++u) {
+      // a channel group at or beyond C reads as zero (C is a multiple of the group size)
+      const int oct = (tid + u * C::THREADS) % C::OCT;
+      const bool ok = u_goff[u] >= 0 && c0 + oct * EPC < Cc;
+#pragma unroll
+      for (int i = 0; i < EPC; ++i) {
+        const uint32_t off = ok ? (uint32_t)((u_goff[u] + (c0 + i) * HW) * ES) : OOB;
+        if (ok && off + 16u > (uint32_t)args.cInBytes) {
+          // the very last vector of the tensor: a 16-byte read would leave the buffer, which
+          // drops the valid part when the start is not dword aligned; fetch element-wise
+          u32x4 v = {0u, 0u, 0u, 0u};
+          for (int e = 0; e < EPC; ++e) {
+            const uint32_t eo = off + e * ES;
+            if (eo + ES <= (uint32_t)args.cInBytes) {
+              if constexpr (ES == 4) v[e] = ((const uint32_t*)args.B)[eo / 4];
+              else v[e >> 1] |= (uint32_t)((const uint16_t*)args.B)[eo / 2] << ((e & 1) * 16);
+            }
+          }
+          u_reg[u][i] = v;
+        } else {
+          u_reg[u][i] = __builtin_amdgcn_raw_buffer_load_b128(rs_in, off, 0, 0);
+        }
+      }
+    }
+  };
+  auto commit_patch = [&](int st) {
+    GENSOR_LDS char* base = lds + st * stage_bytes + a_bytes;
+#pragma unroll
+    for (int u = 0; u < C::UNITS_MAX; ++u) {
+      if (u_goff[u] < 0) continue;                 // rows outside an image stay zero
+#pragma unroll
+      for (int x = 0; x < EPC; ++x) {
+        u32x4 o;                                   // channels i = 0..EPC-1 of pixel x
+        if constexpr (ES == 4) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[i] = u_reg[u][i][x];
+        } else {
+          // 8x8 transpose of 16-bit elements: dword d of the output pairs channels 2d, 2d+1
+#pragma unroll
+          for (int d = 0; d < 4; ++d)
+            o[d] = __builtin_amdgcn_perm(u_reg[u][2 * d + 1][x >> 1], u_reg[u][2 * d][x >> 1],
+                                         (x & 1) ? 0x07060302u : 0x05040100u);
+        }
+        if (x < u_nx[u]) *(GENSOR_LDS u32x4*)(base + u_dst[u] + x * SLOT) = o;
+      }
+    }
+  };
+
+  // ---- fragment addressing
+  const int frow = lane % MB, fgrp = lane / MB;
+  auto block_row = [&](int bi) { return wave_m * C::WM + bi * MB; };
+  auto block_col = [&](int bj) { return wave_n * C::WN + bj * MB; };
+  int b_base[C::NBLK];             // byte offset of the lane's pixel (tap 0,0) inside the patch
+#pragma unroll
+  for (int bj = 0; bj < C::NBLK; ++bj) {
+    int n = n0 + block_col(bj) + frow;
+    n = n < args.N ? n : args.N - 1;
+    const int g = n / Q, q = n - g * Q;
+    const int img = g / P, p = g - img * P;
+    b_base[bj] = ((img * Hp + p * stride - R0) * PW + q * stride) * SLOT;
+  }
+  auto compute = [&](int st) {
+    GENSOR_LDS char* abase = lds + st * stage_bytes;
+    GENSOR_LDS char* pbase = abase + a_bytes;
+    for (int r = 0; r < R; ++r)
+      for (int s = 0; s < S; ++s) {
+        const int tap = (r * PW + s) * SLOT;
+        const int rs = r * S + s;
+#pragma unroll
+        for (int ks = 0; ks < C::KSTEPS_C; ++ks) {
+          const int ch = ks * C::LANE_GROUPS + fgrp;
+          u32x4 af[C::MBLK], bf[C::NBLK];
+#pragma unroll
+          for (int bi = 0; bi < C::MBLK; ++bi)
+            af[bi] = *(GENSOR_LDS u32x4*)(abase + (block_row(bi) + frow) * a_pitch + (rs * C::OCT + ch) * 16);
+#pragma unroll
+          for (int bj = 0; bj < C::NBLK; ++bj) bf[bj] = *(GENSOR_LDS u32x4*)(pbase + b_base[bj] + tap + ch * 16);
+#pragma unroll
+          for (int bi = 0; bi < C::MBLK; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < C::NBLK; ++bj) MF::run(af[bi], bf[bj], acc[bi][bj]);
+        }
+      }
+  };
+
+  // ---- zero both patch buffers once: cells outside the images are never written again
+  {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    const int patch_bytes = stage_bytes - a_bytes;
+    for (int st = 0; st < 2; ++st)
+      for (int o = tid * 16; o < patch_bytes; o += C::THREADS * 16) *(GENSOR_LDS u32x4*)(lds + st * stage_bytes + a_bytes + o) = z;
+  }
+  const int nstages = (Cc + BKC - 1) / BKC;
+  fetch_a(0);
+  fetch_patch(0);
+  __syncthreads();
+  commit_a(0, 0);
+  commit_patch(0);
+  __syncthreads();
+  for (int st = 0; st < nstages; ++st) {
+    const bool more = st + 1 < nstages;
+    if (more) {
+      fetch_a((st + 1) * BKC);
+      fetch_patch((st + 1) * BKC);
+    }
+    compute(st & 1);
+    if (more) {
+      commit_a((st + 1) & 1, (st + 1) * BKC);
+      commit_patch((st + 1) & 1);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: O[img][filter][p][q], row = filter, column = (img, p, q)
+  typedef typename C::OutT OutT;
+  constexpr int OS = ElemSize<OutT>::value;
+  const __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void*)args.C, 0, (uint32_t)args.cOutBytes, RSRC_FLAGS);
+#pragma unroll
+  for (int bj = 0; bj < C::NBLK; ++bj) {
+    const int col = n0 + block_col(bj) + frow;
+    const int img = col / PQ;
+    const int cbase = img * args.M * PQ + (col - img * PQ);
+#pragma unroll
+    for (int bi = 0; bi < C::MBLK; ++bi)
+#pragma unroll
+      for (int v = 0; v < MF::NACC; ++v) {
+        const int rr = (MB == 32) ? 8 * (v / 4) + 4 * fgrp + (v % 4) : 4 * fgrp + v;
+        const int row = m0 + block_row(bi) + rr;
+        const uint32_t off = (row < args.M && col < args.N) ? (uint32_t)((cbase + row * PQ) * OS) : OOB;
+        const float val = acc[bi][bj][v];
+        if constexpr (OS == 4) {
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), rs_out, off, 0, 0);
+        } else {
+          uint16_t bits;
+          store_out<OutT>(&bits, 0, val);
+          __builtin_amdgcn_raw_buffer_store_b16(bits, rs_out, off, 0, 0);
+        }
+      }
+  }
+}
+
+}  // namespace gensor

@@ -47,6 +47,9 @@ struct KernelArgs {
   int32_t panel;                   // tile rows per panel in the workgroup->tile map
   // convolution geometry (B_CONV only)
   int32_t cC, cH, cW, cR, cS, cP, cQ, cStride, cPad;
+  // patch-staged convolution only: images, LDS plan and tensor sizes in bytes (each < 2^31)
+  int32_t cN, cApitch, cPatchRows, cStageBytes;
+  int64_t cInBytes, cWBytes, cOutBytes;
 };
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));

@@ -59,6 +59,8 @@ gensor_status gemm_view(const gensor_problem* p, GemmView* v) {
     v->K = p->c * p->r * p->s;
     v->batch = 1;
     v->bsrc = B_CONV;
+    v->cn = p->n; v->cc = p->c; v->ch = p->h; v->cw = p->w; v->cr = p->r; v->cs = p->s;
+    v->cstride = p->stride; v->cpad = p->pad;
   } else {
     return GENSOR_ERR_INVALID_ARG;
   }
@@ -82,8 +84,46 @@ void schedule_from_instance(const InstanceDesc& d, gensor_schedule* s) {
   s->wg_remap = 4;
 }
 
+bool conv_patch_plan(const InstanceDesc& d, const GemmView& v, ConvPlan* plan) {
+  const int64_t lim = 0x7fffffffll;
+  const int epc = 16 / v.esize;
+  const int64_t rs = v.cr * v.cs;
+  if (rs > 9 || v.cc % epc != 0) return false;
+  ConvPlan pl;
+  pl.in_bytes = v.cn * v.cc * v.ch * v.cw * v.esize;
+  pl.w_bytes = v.M * v.K * v.esize;
+  pl.out_bytes = v.M * v.N * v.osize;
+  if (pl.in_bytes >= lim || pl.w_bytes >= lim || pl.out_bytes >= lim) return false;
+  // filter tile: [bm][rs * bkc] with a row pitch of an odd number of 16-byte chunks
+  int64_t p16 = rs * d.bk * v.esize / 16;
+  if (p16 % 2 == 0) ++p16;
+  pl.a_pitch = (int)(p16 * 16);
+  if ((int64_t)d.bm * pl.a_pitch >= (1 << 20)) return false;
+  // patch rows: the most stacked padded input rows any pixel tile touches
+  const int64_t hp = v.ch + 2 * v.cpad, pw = v.cw + 2 * v.cpad;
+  int64_t rows = 0;
+  for (int64_t n0 = 0; n0 < v.N; n0 += d.bn) {
+    const int64_t n1 = (n0 + d.bn < v.N ? n0 + d.bn : v.N) - 1;
+    const int64_t g0 = n0 / v.Q, g1 = n1 / v.Q;
+    const int64_t r0 = (g0 / v.P) * hp + (g0 % v.P) * v.cstride;
+    const int64_t r1 = (g1 / v.P) * hp + (g1 % v.P) * v.cstride + v.cr - 1;
+    if (r1 - r0 + 1 > rows) rows = r1 - r0 + 1;
+  }
+  pl.patch_rows = (int)rows;
+  const int slot = d.bk * v.esize + 16;
+  const int64_t stage = (int64_t)d.bm * pl.a_pitch + rows * pw * slot;
+  if (2 * stage > 160 * 1024) return false;
+  pl.stage_bytes = (int)stage;
+  const int64_t units = rows * ((v.cw + epc - 1) / epc) * (d.bk / epc);
+  if (units > (int64_t)d.units * d.threads) return false;
+  if (plan) *plan = pl;
+  return true;
+}
+
 bool instance_serves(const InstanceDesc& d, const GemmView& v) {
-  return d.in_dtype == v.in_dtype && d.out_dtype == v.out_dtype && d.bsrc == v.bsrc;
+  if (d.in_dtype != v.in_dtype || d.out_dtype != v.out_dtype || d.bsrc != v.bsrc) return false;
+  if (d.units) return conv_patch_plan(d, v, nullptr);
+  return true;
 }
 
 // Does instance d realise schedule s (same lattice point)?
@@ -112,7 +152,7 @@ bool vector_ok(const GemmView& v, const void* A, int64_t lda, int64_t strideA, c
   if (!al(A) || lda % epc || strideA % epc || v.K % epc) return false;
   if (v.bsrc == B_KC) return al(B) && ldb % epc == 0 && strideB % epc == 0;
   if (v.bsrc == B_NC) return al(B) && ldb % epc == 0 && strideB % epc == 0 && v.N % epc == 0;
-  return true;   // convolution: the gather is element-wise
+  return al(B);  // convolution: the gather is element-wise; the patch path reads 16-byte vectors
 }
 
 }  // namespace gensor
@@ -164,7 +204,7 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
   const InstanceDesc* d = find_instance(s, v);
   if (!d) return GENSOR_ERR_NO_SCHEDULE;
   if (d->vec && !vec_ok) return GENSOR_ERR_NO_SCHEDULE;          // schedule asks for vector accesses the operands cannot give
-  if (d->direct && v.K % d->bk != 0) return GENSOR_ERR_NO_SCHEDULE;
+  if (d->direct && !d->units && v.K % d->bk != 0) return GENSOR_ERR_NO_SCHEDULE;
   if (s->split_k > 1) return GENSOR_ERR_UNSUPPORTED;
   // 32-bit offsets inside one workgroup tile
   const int64_t lim = 0x7fffffffll;
@@ -185,6 +225,13 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
   a.panel = s->wg_remap > 0 ? s->wg_remap : 1;
   if (a.panel > a.tiles_m) a.panel = a.tiles_m;
   if ((int64_t)a.tiles_m * a.tiles_n * a.batch > INT32_MAX) return GENSOR_ERR_UNSUPPORTED;
+  if (d->units) {
+    ConvPlan pl;
+    if (!conv_patch_plan(*d, v, &pl)) return GENSOR_ERR_NO_SCHEDULE;
+    a.cN = (int32_t)p->n; a.cApitch = pl.a_pitch; a.cPatchRows = pl.patch_rows; a.cStageBytes = pl.stage_bytes;
+    a.cInBytes = pl.in_bytes; a.cWBytes = pl.w_bytes; a.cOutBytes = pl.out_bytes;
+    a.batch = 1;
+  }
   if (v.bsrc == B_CONV) {
     a.cC = (int32_t)p->c; a.cH = (int32_t)p->h; a.cW = (int32_t)p->w; a.cR = (int32_t)p->r; a.cS = (int32_t)p->s;
     a.cP = (int32_t)v.P; a.cQ = (int32_t)v.Q; a.cStride = (int32_t)p->stride; a.cPad = (int32_t)p->pad;

@@ -13,7 +13,17 @@ struct GemmView {
   int64_t P, Q;          // convolution output extent
   int in_dtype, out_dtype, esize, osize;
   int bsrc;              // BSrc
+  // convolution geometry (zero otherwise)
+  int64_t cn, cc, ch, cw, cr, cs, cstride, cpad;
 };
+
+// LDS plan of a patch-staged convolution instance for one problem.
+struct ConvPlan {
+  int a_pitch, patch_rows, stage_bytes;
+  int64_t in_bytes, w_bytes, out_bytes;
+};
+// False if instance d (a patch-staged convolution) cannot run the convolution in v.
+bool conv_patch_plan(const InstanceDesc& d, const GemmView& v, ConvPlan* plan);
 
 gensor_status gemm_view(const gensor_problem* p, GemmView* v);
 void schedule_from_instance(const InstanceDesc& d, gensor_schedule* s);

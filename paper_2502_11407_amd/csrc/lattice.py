@@ -8,9 +8,14 @@ BSRC = {"KC": 0, "NC": 1, "CONV": 2}
 CT = {"f32": "f32_t", "f16": "f16_t", "bf16": "bf16_t"}
 
 
-def _inst(dt, out, bm, bn, bk, wm, wn, mb, vm=1, vn=1, bsrc="KC", vec=1, stages=2, direct=0):
+def _inst(dt, out, bm, bn, bk, wm, wn, mb, vm=1, vn=1, bsrc="KC", vec=1, stages=2, direct=0, units=0):
     return dict(dt=dt, out=out, bm=bm, bn=bn, bk=bk, wm=wm, wn=wn, mb=mb, vm=vm, vn=vn,
-                bsrc=bsrc, vec=vec, stages=stages, direct=direct)
+                bsrc=bsrc, vec=vec, stages=stages, direct=direct, units=units)
+
+
+def _convp(dt, out, bm, bn, bkc, wm, wn, units):
+    """Convolution with the input patch staged in LDS (direct = 1 on the CONV source); bk = channels per stage."""
+    return _inst(dt, out, bm, bn, bkc, wm, wn, 32, 1, 1, "CONV", 1, 2, 1, units)
 
 
 def lattice():
@@ -55,6 +60,14 @@ def lattice():
         out.append(_inst(dt, dt, 64, 64, 32, 32, 32, 16, 1, 1, "NC", vec=0))
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "CONV"))
         out.append(_inst(dt, dt, 64, 64, 32, 32, 32, 16, 1, 1, "CONV", vec=0))
+        # patch-staged convolution: (BM filters, BN pixels, channels per stage, WM, WN, units)
+        for (bm, bn, bkc, wm, wn, units) in [(64, 256, 16, 64, 64, 1), (64, 128, 16, 32, 64, 1), (64, 64, 16, 32, 32, 1),
+                                             (128, 128, 16, 64, 64, 1), (128, 256, 16, 64, 64, 1), (256, 128, 16, 64, 64, 1),
+                                             (32, 256, 16, 32, 64, 1), (64, 256, 16, 64, 64, 2), (128, 128, 16, 64, 64, 2)]:
+            out.append(_convp(dt, "f32", bm, bn, bkc, wm, wn, units))
+        out.append(_convp(dt, dt, 64, 128, 16, 32, 64, 1))
+    for (bm, bn, bkc, wm, wn, units) in [(64, 128, 8, 32, 64, 1), (64, 64, 8, 32, 32, 1), (128, 128, 8, 64, 64, 2)]:
+        out.append(_convp("f32", "f32", bm, bn, bkc, wm, wn, units))
     tiles32 = [
         (128, 128, 32, 64, 64, 32, 1, 1),
         (128, 128, 32, 64, 64, 32, 2, 2),
@@ -73,6 +86,9 @@ def lattice():
 
 
 def cfg_type(d):
+    if d["units"]:
+        return "ConvCfg<%s, %s, %d, %d, %d, %d, %d, %d, %d>" % (
+            CT[d["dt"]], CT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"], d["units"])
     return ("Cfg<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s, %d, %s>" % (
         CT[d["dt"]], CT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"], d["vm"], d["vn"],
         BSRC[d["bsrc"]], "true" if d["vec"] else "false", d["stages"], "true" if d["direct"] else "false"))

@@ -3,6 +3,7 @@
 // staging mode, vector width) for one element type and operand source.
 #pragma once
 #include <hip/hip_runtime.h>
+#include "conv_kernel.hpp"
 #include "gemm_kernel.hpp"
 
 namespace gensor {
@@ -13,7 +14,8 @@ struct InstanceDesc {
   int bm, bn, bk, wm, wn, mb, vm, vn;
   int bsrc;                             // BSrc
   int vec, stages, direct;
-  int lds_bytes, threads, kg;           // kg: k consumed per fragment read
+  int lds_bytes, threads, kg;           // kg: k consumed per fragment read (lds_bytes 0: set per problem)
+  int units;                            // patch-staged convolution: transpose units per thread
   hipError_t (*launch)(const KernelArgs&, hipStream_t);
 };
 
@@ -31,6 +33,21 @@ hipError_t launch_instance(const KernelArgs& a, hipStream_t st) {
   }
   const unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.batch;
   hipLaunchKernelGGL(contraction_kernel<C>, dim3(grid), dim3(C::THREADS), C::LDS_BYTES, st, a);
+  return hipGetLastError();
+}
+
+// patch-staged convolution: the LDS size depends on the problem (a.cStageBytes, two stages)
+template <typename C>
+hipError_t launch_conv_instance(const KernelArgs& a, hipStream_t st) {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)conv_patch_kernel<C>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n;
+  hipLaunchKernelGGL(conv_patch_kernel<C>, dim3(grid), dim3(C::THREADS), 2 * a.cStageBytes, st, a);
   return hipGetLastError();
 }
 

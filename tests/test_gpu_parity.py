@@ -51,9 +51,11 @@ def instance_cases(gs):
     for idx in range(gs.num_instances()):
         for dt in ("f32", "f16", "bf16"):
             for out_dt in sorted({"f32", dt}):
-                for tb, op in ((1, "gemm"), (0, "gemm"), (0, "conv")):
-                    p = (gs.conv_problem(dt, 1, 8, 8, 8, 8, 3, 3, 1, 1, out_dt) if op == "conv"
-                         else gs.gemm_problem(dt, 64, 64, 64, 0, tb, 1, out_dt))
+                for tb, op in ((1, "gemm"), (0, "gemm"), (0, "conv"), (0, "conv1x1")):
+                    if op == "conv1x1" and out and out[-1][0] == idx:
+                        continue                      # already covered with 3x3 filters
+                    p = (gs.conv_problem(dt, 1, 8, 8, 8, 8, 3 if op == "conv" else 1, 3 if op == "conv" else 1, 1, 1, out_dt)
+                         if op.startswith("conv") else gs.gemm_problem(dt, 64, 64, 64, 0, tb, 1, out_dt))
                     s = gs.instance_schedule(idx, p)
                     if s is not None:
                         out.append((idx, dt, out_dt, op, tb, s))
@@ -81,6 +83,8 @@ def test_every_instance_bit_exact_on_integers(gs):
         else:
             import torch
             c, r = (8, 3) if vec else (5, 3)        # K = c*r*r: 72 (whole chunks) or 45
+            if op == "conv1x1":
+                c, r = 24, 1
             k = bm + 5
             n, h, w = 2, 9, max(7, bn // 8)
             I = inputs.small_ints(300 + idx, (n, c, h, w), dt, -min(lim, 2), min(lim, 2))
@@ -168,6 +172,41 @@ def test_conv_geometry_bit_exact(gs, stride, pad, r, s):
     gs.conv2d(p, gs.to_device(I, "f16"), gs.to_device(W, "f16"), dO)
     torch.cuda.synchronize()
     assert np.array_equal(gs.to_host_f64(dO), want)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("geom", [
+    # n, c, h, w, k, r, s, stride, pad
+    (3, 24, 13, 11, 70, 3, 3, 1, 1),     # channel tail (24 = 16 + 8), W not a multiple of 8, tiles span images
+    (2, 16, 9, 20, 33, 3, 3, 2, 1),      # stride 2
+    (2, 40, 12, 12, 64, 1, 1, 2, 0),     # 1x1 stride 2, no padding
+    (1, 8, 7, 30, 16, 1, 3, 1, 2),       # 1x3 filter, padding wider than the filter needs
+    (4, 32, 6, 6, 130, 3, 3, 1, 0),      # valid convolution, tiny images: a tile covers several images
+    (2, 16, 16, 16, 64, 2, 2, 1, 1),     # even filter
+])
+def test_conv_patch_instances_bit_exact(gs, dtype, geom):
+    """Every patch-staged convolution instance that can run the geometry, bit-exact on integers."""
+    import torch
+    n, c, h, w, k, r, s, stride, pad = geom
+    I = inputs.small_ints(11, (n, c, h, w), dtype, -2, 2)
+    W = inputs.small_ints(12, (k, c, r, s), dtype, -2, 2)
+    want = ops.conv2d(I, W, dtype, stride=stride, pad=pad)
+    p = gs.conv_problem(dtype, n, c, h, w, k, r, s, stride, pad)
+    dI, dW = gs.to_device(I, dtype), gs.to_device(W, dtype)
+    ran = 0
+    for idx in range(gs.num_instances()):
+        sch = gs.instance_schedule(idx, p)
+        if sch is None or not sch.direct_lds:
+            continue
+        print(f"conv patch instance {idx} tile {sch.tile[0][0]}x{sch.tile[1][0]}x{sch.tile[2][0]} geom {geom} {dtype}", flush=True)
+        dO = gs.empty_device(want.shape)
+        dO.fill_(float("nan"))
+        gs.conv2d(p, dI, dW, dO, sch)
+        torch.cuda.synchronize()
+        got = gs.to_host_f64(dO)
+        assert np.array_equal(got, want), f"instance {idx}: max abs diff {np.nanmax(np.abs(got - want))}"
+        ran += 1
+    assert ran >= 2
 
 
 def test_error_paths_launch_nothing(gs):
