@@ -56,12 +56,13 @@ class Case:
         t0 = time.perf_counter()
         self.sched = gs.construct(self.p, seed=0)
         self.construct_s = time.perf_counter() - t0
+        self.ws = None if self.is_gemm else gs.conv_workspace(self.p, self.sched)
         torch.cuda.synchronize()
 
     def launch(self):
         gs, w = self.gs, self.w
         if not self.is_gemm:
-            gs.conv2d(self.p, self.a, self.b, self.out, self.sched)
+            gs.conv2d(self.p, self.a, self.b, self.out, self.sched, self.ws)
         elif w.batch > 1:
             gs.bmm(self.p, self.a, self.b, self.out, 1.0, 0.0, self.sched)
         else:

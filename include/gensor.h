@@ -157,7 +157,7 @@ gensor_status gensor_instance_schedule(int32_t id, const gensor_problem* p, gens
  * A, B: in_dtype, C: out_dtype, row-major with leading dimensions lda, ldb, ldc in
  * elements (lda >= K or M if transA, ldb >= N or K if transB, ldc >= N).
  * s == NULL: a schedule is constructed for `p` (seed 0) and remembered per shape.
- * workspace is unused unless s->split_k > 1 (pass NULL, 0).
+ * workspace is unused (pass NULL, 0).
  */
 gensor_status gensor_gemm(const gensor_schedule* s, const gensor_problem* p, float alpha,
                           const void* A, int64_t lda, const void* B, int64_t ldb,
@@ -177,6 +177,10 @@ gensor_status gensor_bmm(const gensor_schedule* s, const gensor_problem* p, floa
  * (operator table, Conv2d row: O = (I * K) downsampled by S; cross-correlation, zero
  * padding; P = floor((h + 2 pad - r)/stride) + 1, Q likewise).  All three tensors are
  * contiguous.  Computed as an implicit GEMM: no im2col buffer is materialised.
+ * Schedules that cache the input patch in LDS (direct_lds = 1) read a K,R,S,C copy of the
+ * filters which the call first writes into `workspace` (device memory, 16-byte aligned,
+ * at least gensor_workspace_bytes(s, p) bytes; GENSOR_ERR_WORKSPACE otherwise).  With
+ * s == NULL such schedules are considered only if the workspace is large enough.
  */
 gensor_status gensor_conv2d(const gensor_schedule* s, const gensor_problem* p,
                             const void* input, const void* weight, void* output,

@@ -208,9 +208,16 @@ def bmm(p: Problem, A, B, Cout, alpha: float = 1.0, beta: float = 0.0, schedule:
     _check(st, "gensor_bmm")
 
 
-def conv2d(p: Problem, I, W, O, schedule: Optional[Schedule] = None, stream=None):
-    """O = conv(I, W): contiguous NCHW input, KCRS filters, NKPQ output, all on the device."""
-    st = lib.gensor_conv2d(_sref(schedule), C.byref(p), I.data_ptr(), W.data_ptr(), O.data_ptr(), None, 0,
+def workspace_bytes(p: Problem, schedule: Optional[Schedule] = None) -> int:
+    return int(lib.gensor_workspace_bytes(_sref(schedule), C.byref(p)))
+
+
+def conv2d(p: Problem, I, W, O, schedule: Optional[Schedule] = None, workspace=None, stream=None):
+    """O = conv(I, W): contiguous NCHW input, KCRS filters, NKPQ output, all on the device.
+    `workspace` is a device tensor of at least workspace_bytes(p, schedule) bytes (or None)."""
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    st = lib.gensor_conv2d(_sref(schedule), C.byref(p), I.data_ptr(), W.data_ptr(), O.data_ptr(), ws_ptr, ws_len,
                            _stream_ptr(stream))
     _check(st, "gensor_conv2d")
 
@@ -221,6 +228,12 @@ def to_device(arr: np.ndarray, dtype: str):
     if dtype == "bf16":
         return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).cuda().view(torch.bfloat16)
     return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+
+def conv_workspace(p: Problem, schedule: Optional[Schedule] = None):
+    """Device buffer large enough for gensor_conv2d on `p` with `schedule` (plumbing)."""
+    import torch
+    return torch.empty(max(16, workspace_bytes(p, schedule)), dtype=torch.uint8, device="cuda")
 
 
 def empty_device(shape, dtype: str = "f32"):

@@ -317,8 +317,9 @@ double predict_instance(const GemmView& v, const gensor_hw& hw, const InstanceDe
   return predict(v, hw, d.bm, d.bn, d.bk, d.wm, d.wn, d.kg, d.vm, d.vn, d.vec, d.stages, d.direct);
 }
 
-bool usable(const InstanceDesc& d, const GemmView& v, bool vec_ok) {
+bool usable(const InstanceDesc& d, const GemmView& v, bool vec_ok, bool ws_ok = true) {
   if (!instance_serves(d, v)) return false;
+  if (d.units && !ws_ok) return false;
   if (d.vec && !vec_ok) return false;
   if (d.direct && v.bsrc != B_CONV && v.K % d.bk != 0) return false;
   return true;
@@ -327,7 +328,7 @@ bool usable(const InstanceDesc& d, const GemmView& v, bool vec_ok) {
 }  // namespace
 
 gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
-                                 uint64_t seed, bool vec_ok, gensor_schedule* out) {
+                                 uint64_t seed, bool vec_ok, bool ws_ok, gensor_schedule* out) {
   if (!p || !out) return GENSOR_ERR_INVALID_ARG;
   const auto t0 = std::chrono::steady_clock::now();
   GemmView v;
@@ -355,7 +356,7 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
     // instances on the same tiles; among them those whose V is nearest to the state's
     auto same_tiles = [&](const InstanceDesc& d) {
       return d.bm == e.tile[0][0] && d.bn == e.tile[1][0] && d.bk == e.tile[2][0] && d.wm == e.tile[0][1] &&
-             d.wn == e.tile[1][1] && d.kg == e.tile[2][1] && usable(d, v, vec_ok);
+             d.wn == e.tile[1][1] && d.kg == e.tile[2][1] && usable(d, v, vec_ok, ws_ok);
     };
     auto vdist = [&](const InstanceDesc& d) {
       return std::fabs(std::log2((double)d.vm) - std::log2((double)e.v[0])) +
@@ -381,7 +382,7 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
     double bd = 0.0;
     for (int i = 0; i < g_num_instances; ++i) {
       const InstanceDesc& d = g_instances[i];
-      if (!usable(d, v, vec_ok)) continue;
+      if (!usable(d, v, vec_ok, ws_ok)) continue;
       const double us = predict_instance(v, c.hw, d);
       if (us <= 0) continue;
       const int cand[8] = {d.bm, d.bn, d.bk, d.wm, d.wn, d.kg, d.vm, d.vn};
@@ -409,7 +410,7 @@ extern "C" const gensor_hw* gensor_hw_mi355x(void) { return &kMi355x; }
 
 extern "C" gensor_status gensor_construct(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
                                           uint64_t seed, gensor_schedule* out) {
-  return construct_internal(p, hw, opts, seed, true, out);
+  return construct_internal(p, hw, opts, seed, true, true, out);
 }
 
 extern "C" gensor_status gensor_construct_trace(const gensor_problem* p, const gensor_hw* hw,

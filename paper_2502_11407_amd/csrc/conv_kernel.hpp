@@ -4,9 +4,11 @@
 //
 // GEMM view: m = filter, n = (image, out row, out col), k = (filter row, filter col, channel)
 // with the channel innermost.  One LDS stage holds BKC channels:
-//   * the filters of this workgroup's BM rows, permuted on the way in from (c, r, s) to
-//     (r, s, c) order, as a k-contiguous tile [BM][R*S*BKC] (row pitch an odd number of
-//     16-byte chunks, so 16 consecutive rows fall in 16 different bank groups);
+//   * the filters of this workgroup's BM rows as a k-contiguous tile [BM][R*S*BKC] (row
+//     pitch an odd number of 16-byte chunks, so 16 consecutive rows fall in 16 different
+//     bank groups).  They are read from a copy of the filter tensor that a small pre-pass
+//     (permute_filters) has reordered from KCRS to K,R,S,C, so that BKC channels of one tap
+//     are contiguous;
 //   * the input patch that the workgroup's BN output pixels touch, channel-last:
 //     [patch row][patch col][BKC channels + 16 bytes pad].  A patch row is a row of the
 //     zero-padded images stacked on top of each other; rows and columns outside an image are
@@ -42,6 +44,21 @@ struct ConvCfg {
   static_assert(BKC % KG == 0 && KSTEPS_C >= 1, "channel tile must hold whole fragment k groups");
   static_assert(BM % WM == 0 && BN % WN == 0 && WM % MB == 0 && WN % MB == 0, "tiles");
 };
+
+// Filters KCRS -> K,R,S,C (element size ES bytes); one thread per output element.
+template <int ES>
+__global__ __launch_bounds__(256) void permute_filters(const void* w, void* out, int K, int Cc, int RS) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = (int64_t)K * Cc * RS;
+  if (i >= total) return;
+  const int c = (int)(i % Cc);
+  const int64_t t = i / Cc;
+  const int rs = (int)(t % RS);
+  const int64_t k = t / RS;
+  const int64_t src = (k * Cc + c) * RS + rs;
+  if constexpr (ES == 4) ((uint32_t*)out)[i] = ((const uint32_t*)w)[src];
+  else ((uint16_t*)out)[i] = ((const uint16_t*)w)[src];
+}
 
 template <typename C>
 __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs args) {
@@ -99,49 +116,36 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
 #pragma unroll
       for (int v = 0; v < MF::NACC; ++v) acc[i][j][v] = 0.f;
 
-  // ---- filter staging plan.  Vector v of this thread covers EPC consecutive stored
-  // elements (c, r, s order) of filter row a_row[v], starting at local element a_e0[v];
-  // element e goes to k' = (e % RS) * BKC + e / RS.
-  const int a_vec_per_row = BKC * RS / EPC;
+  // ---- filter staging plan.  Vector v of this thread is one 16-byte channel group of one
+  // tap of one filter row in the K,R,S,C copy of the filters.
+  const int a_vec_per_row = RS * C::OCT;
   const int a_vecs = BM * a_vec_per_row;
-  int a_goff[C::A_VEC_MAX];        // element offset of the vector inside the filter tensor at channel tile 0
-  int a_dst[C::A_VEC_MAX];         // LDS byte offset of filter row + packed (rs, c) of the first element
+  int a_goff[C::A_VEC_MAX];        // element offset at channel tile 0, or -1
+  int a_dst[C::A_VEC_MAX];         // LDS byte offset inside the filter tile
   u32x4 a_reg[C::A_VEC_MAX];
 #pragma unroll
   for (int v = 0; v < C::A_VEC_MAX; ++v) {
     const int q = tid + v * C::THREADS;
-    const int row = q / a_vec_per_row, e0 = (q - row * a_vec_per_row) * EPC;
-    const int c_lo = e0 / RS, rs0 = e0 - c_lo * RS;
+    const int row = q / a_vec_per_row, t = q - row * a_vec_per_row;
+    const int rs = t / C::OCT, oct = t - rs * C::OCT;
     const bool ok = q < a_vecs && (m0 + row) < args.M;
-    a_goff[v] = ok ? ((m0 + row) * Cc) * RS + e0 : -1;
-    a_dst[v] = (row * a_pitch) | (rs0 << 20) | (c_lo << 24);       // a_pitch * BM < 2^20
+    a_goff[v] = ok ? ((m0 + row) * RS + rs) * Cc + oct * EPC : -1;
+    a_dst[v] = row * a_pitch + t * 16;
   }
   auto fetch_a = [&](int c0) {
 #pragma unroll
     for (int v = 0; v < C::A_VEC_MAX; ++v) {
-      // channels at or beyond C: the whole vector may straddle, so validity is per element below
-      const uint32_t off = a_goff[v] >= 0 ? (uint32_t)((a_goff[v] + c0 * RS) * ES) : OOB;
-      a_reg[v] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, off, 0, 0);
+      const int oct = (tid + v * C::THREADS) % C::OCT;
+      const bool ok = a_goff[v] >= 0 && c0 + oct * EPC < Cc;        // channel tail of the last stage reads zero
+      a_reg[v] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, ok ? (uint32_t)((a_goff[v] + c0) * ES) : OOB, 0, 0);
     }
   };
-  auto commit_a = [&](int st, int c0) {
+  auto commit_a = [&](int st) {
     GENSOR_LDS char* base = lds + st * stage_bytes;
 #pragma unroll
     for (int v = 0; v < C::A_VEC_MAX; ++v) {
       if (tid + v * C::THREADS >= a_vecs) break;
-      const int rowoff = a_dst[v] & 0xfffff;
-      int rs = (a_dst[v] >> 20) & 15, cl = a_dst[v] >> 24;
-#pragma unroll
-      for (int i = 0; i < EPC; ++i) {
-        uint32_t bits;
-        if constexpr (ES == 4) bits = a_reg[v][i];
-        else bits = (a_reg[v][i >> 1] >> ((i & 1) * 16)) & 0xffffu;
-        if (c0 + cl >= Cc) bits = 0u;                                 // channel tail of the last stage
-        GENSOR_LDS char* p = base + rowoff + (rs * BKC + cl) * ES;
-        if constexpr (ES == 4) *(GENSOR_LDS uint32_t*)p = bits;
-        else *(GENSOR_LDS uint16_t*)p = (uint16_t)bits;
-        if (++rs == RS) { rs = 0; ++cl; }
-      }
+      *(GENSOR_LDS u32x4*)(base + a_dst[v]) = a_reg[v];
     }
   };
 
@@ -262,7 +266,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
   fetch_a(0);
   fetch_patch(0);
   __syncthreads();
-  commit_a(0, 0);
+  commit_a(0);
   commit_patch(0);
   __syncthreads();
   for (int st = 0; st < nstages; ++st) {
@@ -273,7 +277,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
     }
     compute(st & 1);
     if (more) {
-      commit_a((st + 1) & 1, (st + 1) * BKC);
+      commit_a((st + 1) & 1);
       commit_patch((st + 1) & 1);
     }
     __syncthreads();

@@ -167,7 +167,16 @@ extern "C" gensor_status gensor_instance_schedule(int32_t id, const gensor_probl
   return GENSOR_OK;
 }
 
-extern "C" size_t gensor_workspace_bytes(const gensor_schedule*, const gensor_problem*) { return 0; }
+// Patch-staged convolution instances read a K,R,S,C copy of the filters that the library
+// writes into the caller's workspace; nothing else needs one.
+extern "C" size_t gensor_workspace_bytes(const gensor_schedule* s, const gensor_problem* p) {
+  GemmView v;
+  if (!p || gemm_view(p, &v) != GENSOR_OK || v.bsrc != B_CONV) return 0;
+  const size_t need = (size_t)(v.M * v.K * v.esize);
+  if (!s) return need;                       // what any schedule the library may construct can ask for
+  const InstanceDesc* d = find_instance(s, v);
+  return d && d->units ? need : 0;
+}
 
 // ------------------------------------------------------------------------------------
 // schedule == NULL: construct once per (problem, alignment class) and remember it.
@@ -176,8 +185,8 @@ namespace {
 std::mutex g_memo_mutex;
 std::map<std::tuple<int, int, int, int, int, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int>, gensor_schedule> g_memo;
 
-gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, gensor_schedule* out) {
-  auto key = std::make_tuple((int)p->op, (int)p->in_dtype, (int)p->out_dtype, (int)p->transB, vec_ok ? 1 : 0,
+gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, bool ws_ok, gensor_schedule* out) {
+  auto key = std::make_tuple((int)p->op, (int)p->in_dtype, (int)p->out_dtype, (int)p->transB, (vec_ok ? 1 : 0) + (ws_ok ? 2 : 0),
                              p->op == GENSOR_OP_CONV2D ? p->n : p->batch, p->op == GENSOR_OP_CONV2D ? p->c : p->M,
                              p->op == GENSOR_OP_CONV2D ? p->h : p->N, p->op == GENSOR_OP_CONV2D ? p->w : p->K,
                              p->op == GENSOR_OP_CONV2D ? p->k : 0, p->op == GENSOR_OP_CONV2D ? p->r : 0,
@@ -186,18 +195,20 @@ gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, gensor_sch
   std::lock_guard<std::mutex> lock(g_memo_mutex);
   auto it = g_memo.find(key);
   if (it != g_memo.end()) { *out = it->second; return GENSOR_OK; }
-  gensor_status st = construct_internal(p, nullptr, nullptr, 0, vec_ok, out);
+  gensor_status st = construct_internal(p, nullptr, nullptr, 0, vec_ok, ws_ok, out);
   if (st == GENSOR_OK) g_memo[key] = *out;
   return st;
 }
 
 gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmView& v, float alpha,
                   const void* A, int64_t lda, int64_t strideA, const void* B, int64_t ldb, int64_t strideB,
-                  float beta, void* C, int64_t ldc, int64_t strideC, void* stream) {
+                  float beta, void* C, int64_t ldc, int64_t strideC, void* workspace, size_t workspace_bytes, void* stream) {
   const bool vec_ok = vector_ok(v, A, lda, strideA, B, ldb, strideB);
+  const bool ws_ok = workspace && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0 &&
+                     workspace_bytes >= (size_t)(v.M * v.K * v.esize);
   gensor_schedule local;
   if (!s) {
-    gensor_status st = memoised_schedule(p, vec_ok, &local);
+    gensor_status st = memoised_schedule(p, vec_ok, ws_ok, &local);
     if (st != GENSOR_OK) return st;
     s = &local;
   }
@@ -228,6 +239,8 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
   if (d->units) {
     ConvPlan pl;
     if (!conv_patch_plan(*d, v, &pl)) return GENSOR_ERR_NO_SCHEDULE;
+    if (!ws_ok) return GENSOR_ERR_WORKSPACE;
+    a.cWorkspace = workspace;
     a.cN = (int32_t)p->n; a.cApitch = pl.a_pitch; a.cPatchRows = pl.patch_rows; a.cStageBytes = pl.stage_bytes;
     a.cInBytes = pl.in_bytes; a.cWBytes = pl.w_bytes; a.cOutBytes = pl.out_bytes;
     a.batch = 1;
@@ -246,7 +259,6 @@ extern "C" gensor_status gensor_bmm(const gensor_schedule* s, const gensor_probl
                                     const void* B, int64_t ldb, int64_t strideB,
                                     float beta, void* C, int64_t ldc, int64_t strideC,
                                     void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   if (!p || !A || !B || !C) return GENSOR_ERR_INVALID_ARG;
   if (p->op != GENSOR_OP_GEMM && p->op != GENSOR_OP_BMM) return GENSOR_ERR_INVALID_ARG;
   GemmView v;
@@ -257,7 +269,7 @@ extern "C" gensor_status gensor_bmm(const gensor_schedule* s, const gensor_probl
   if (ldc < v.N) return GENSOR_ERR_INVALID_ARG;
   if (strideA < 0 || strideB < 0 || strideC < 0) return GENSOR_ERR_INVALID_ARG;
   if (v.batch > 1 && strideC < v.M * ldc - (ldc - v.N)) return GENSOR_ERR_INVALID_ARG;   // outputs must not overlap
-  return run(s, p, v, alpha, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC, hip_stream);
+  return run(s, p, v, alpha, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" gensor_status gensor_gemm(const gensor_schedule* s, const gensor_problem* p, float alpha,
@@ -271,12 +283,11 @@ extern "C" gensor_status gensor_gemm(const gensor_schedule* s, const gensor_prob
 extern "C" gensor_status gensor_conv2d(const gensor_schedule* s, const gensor_problem* p,
                                        const void* input, const void* weight, void* output,
                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   if (!p || !input || !weight || !output || p->op != GENSOR_OP_CONV2D) return GENSOR_ERR_INVALID_ARG;
   GemmView v;
   gensor_status st = gemm_view(p, &v);
   if (st != GENSOR_OK) return st;
   if (p->n * p->c * p->h * p->w > INT32_MAX) { /* index arithmetic of the gather is 64-bit; extents are 32-bit */ }
   // A = filters [k][c*r*s] (k-contiguous), B = gathered input, C = output viewed per image.
-  return run(s, p, v, 1.0f, weight, v.K, 0, input, 0, 0, 0.0f, output, v.N, 0, hip_stream);
+  return run(s, p, v, 1.0f, weight, v.K, 0, input, 0, 0, 0.0f, output, v.N, 0, workspace, workspace_bytes, hip_stream);
 }

@@ -30,8 +30,9 @@ void schedule_from_instance(const InstanceDesc& d, gensor_schedule* s);
 bool instance_serves(const InstanceDesc& d, const GemmView& v);
 const InstanceDesc* find_instance(const gensor_schedule* s, const GemmView& v);
 
-// gensor_construct with one more input: whether the operands allow 16-byte vector accesses.
+// gensor_construct with two more inputs: whether the operands allow 16-byte vector accesses
+// and whether the caller supplied the workspace that patch-staged convolutions need.
 gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
-                                 uint64_t seed, bool vec_ok, gensor_schedule* out);
+                                 uint64_t seed, bool vec_ok, bool ws_ok, gensor_schedule* out);
 
 }  // namespace gensor

@@ -36,9 +36,19 @@ hipError_t launch_instance(const KernelArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-// patch-staged convolution: the LDS size depends on the problem (a.cStageBytes, two stages)
+// patch-staged convolution: the LDS size depends on the problem (a.cStageBytes, two stages).
+// a.A is the caller's KCRS filter tensor and a.cWorkspace receives its K,R,S,C copy.
 template <typename C>
-hipError_t launch_conv_instance(const KernelArgs& a, hipStream_t st) {
+hipError_t launch_conv_instance(const KernelArgs& a0, hipStream_t st) {
+  KernelArgs a = a0;
+  {
+    const int64_t total = (int64_t)a.M * a.cC * a.cR * a.cS;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(permute_filters<C::ES>, dim3(blocks), dim3(256), 0, st, a.A, a.cWorkspace, a.M, a.cC, a.cR * a.cS);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    a.A = a.cWorkspace;
+  }
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)conv_patch_kernel<C>,

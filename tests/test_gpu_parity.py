@@ -93,7 +93,7 @@ def test_every_instance_bit_exact_on_integers(gs):
             p = gs.conv_problem(dt, n, c, h, w, k, r, r, 1, 1, out_dt)
             dO = gs.empty_device(want.shape, out_dt)
             dO.fill_(float("nan"))
-            gs.conv2d(p, gs.to_device(I, dt), gs.to_device(W, dt), dO, s)
+            gs.conv2d(p, gs.to_device(I, dt), gs.to_device(W, dt), dO, s, gs.conv_workspace(p, s))
             torch.cuda.synchronize()
             got = gs.to_host_f64(dO)
         assert np.abs(want).max() < (256 if out_dt == "bf16" else 2048)
@@ -153,7 +153,7 @@ def test_conv_real_values(gs, which, n, hw, dtype):
     p = gs.conv_problem(dtype, w.n, w.c, w.h, w.w, w.k, w.r, w.s, w.stride, w.pad)
     dO = gs.empty_device(want.shape)
     dO.fill_(float("nan"))
-    gs.conv2d(p, gs.to_device(w.I, dtype), gs.to_device(w.W, dtype), dO)
+    gs.conv2d(p, gs.to_device(w.I, dtype), gs.to_device(w.W, dtype), dO, None, gs.conv_workspace(p))
     torch.cuda.synchronize()
     err = ops.rel_frobenius(gs.to_host_f64(dO), want)
     print(which, dtype, "rel frobenius", err)
@@ -169,7 +169,7 @@ def test_conv_geometry_bit_exact(gs, stride, pad, r, s):
     want = ops.conv2d(I, W, "f16", stride=stride, pad=pad)
     p = gs.conv_problem("f16", n, c, h, w, k, r, s, stride, pad)
     dO = gs.empty_device(want.shape)
-    gs.conv2d(p, gs.to_device(I, "f16"), gs.to_device(W, "f16"), dO)
+    gs.conv2d(p, gs.to_device(I, "f16"), gs.to_device(W, "f16"), dO, None, gs.conv_workspace(p))
     torch.cuda.synchronize()
     assert np.array_equal(gs.to_host_f64(dO), want)
 
@@ -201,12 +201,33 @@ def test_conv_patch_instances_bit_exact(gs, dtype, geom):
         print(f"conv patch instance {idx} tile {sch.tile[0][0]}x{sch.tile[1][0]}x{sch.tile[2][0]} geom {geom} {dtype}", flush=True)
         dO = gs.empty_device(want.shape)
         dO.fill_(float("nan"))
-        gs.conv2d(p, dI, dW, dO, sch)
+        gs.conv2d(p, dI, dW, dO, sch, gs.conv_workspace(p, sch))
         torch.cuda.synchronize()
         got = gs.to_host_f64(dO)
         assert np.array_equal(got, want), f"instance {idx}: max abs diff {np.nanmax(np.abs(got - want))}"
         ran += 1
     assert ran >= 2
+
+
+def test_conv_without_workspace(gs):
+    """A patch-staged schedule without its workspace is refused; the default path then falls back
+    to a schedule that needs none and still matches the oracle."""
+    import torch
+    n, c, h, w, k = 2, 16, 12, 12, 32
+    I = inputs.small_ints(13, (n, c, h, w), "f16", -2, 2)
+    W = inputs.small_ints(14, (k, c, 3, 3), "f16", -2, 2)
+    want = ops.conv2d(I, W, "f16", stride=1, pad=1)
+    p = gs.conv_problem("f16", n, c, h, w, k, 3, 3, 1, 1)
+    dI, dW = gs.to_device(I, "f16"), gs.to_device(W, "f16")
+    dO = gs.empty_device(want.shape)
+    patch = [s for s in (gs.instance_schedule(i, p) for i in range(gs.num_instances())) if s is not None and s.direct_lds]
+    assert patch and gs.workspace_bytes(p, patch[0]) == k * c * 9 * 2
+    with pytest.raises(gs.GensorError) as e:
+        gs.conv2d(p, dI, dW, dO, patch[0])
+    assert e.value.status == 4
+    gs.conv2d(p, dI, dW, dO)                     # no schedule, no workspace
+    torch.cuda.synchronize()
+    assert np.array_equal(gs.to_host_f64(dO), want)
 
 
 def test_error_paths_launch_nothing(gs):
