@@ -49,9 +49,10 @@ Readings (the paper is silent or garbled here)
              keeps each such visited state in its completed form; policy 1 keeps it with
              the printed probability 1 - 1/(1 + exp(-0.5 (-ln T - 10)))
   pick       kept complete states are ranked by the analytical cost model below.  A state is
-             realised by the compiled instances on the same six tile sizes whose V is nearest to
-             its own; the best such instance over all kept states wins (if none exists, the
-             instance nearest to the best-ranked state)
+             realised by every compiled instance on the same spatial tiles (T_2 and T_1 of m and
+             n: the sizes Eq. 1's traffic depends on); k tile, MFMA depth, V and staging mode are
+             then those of the instance.  The best such instance over all kept states wins (if
+             none exists, the instance nearest to the best-ranked state)
 """
 from __future__ import annotations
 
@@ -435,12 +436,12 @@ def pick(view: View, hw: Hw, kept: Sequence[State], instances: Sequence[Instance
         bm, bn, bk = s.tile[0][0], s.tile[1][0], s.tile[2][0]
         wm, wn, kg = s.tile[0][1], s.tile[1][1], s.tile[2][1]
         scored += 1
-        # instances on the same tiles; among them those whose V is nearest to the state's
-        same = [i for i in instances if (i.bm, i.bn, i.bk, i.wm, i.wn, i.kg) == (bm, bn, bk, wm, wn, kg)
-                and (vec_ok or not i.vec) and (not i.direct or view.bsrc == 2 or view.K % i.bk == 0)]
-        vdist = [abs(math.log2(i.vm) - math.log2(s.v[0])) + abs(math.log2(i.vn) - math.log2(s.v[1])) for i in same]
-        for i, dv in zip(same, vdist):
-            if dv != min(vdist):
+        # every compiled instance on the same spatial tiles (T_2 and T_1 of m and n) realises the
+        # state; its k tile, MFMA depth, V and staging mode are whatever was compiled
+        for i in instances:
+            if (i.bm, i.bn, i.wm, i.wn) != (bm, bn, wm, wn) or (i.vec and not vec_ok):
+                continue
+            if i.direct and view.bsrc != 2 and view.K % i.bk != 0:
                 continue
             us = predict_us(view, hw, i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn, i.vec, i.stages, i.direct)
             if us > 0 and (best is None or us < best_us):

@@ -353,21 +353,12 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
   for (const Etir& e : kept) {
     if (!seen.insert(e).second) continue;
     ++scored;
-    // instances on the same tiles; among them those whose V is nearest to the state's
-    auto same_tiles = [&](const InstanceDesc& d) {
-      return d.bm == e.tile[0][0] && d.bn == e.tile[1][0] && d.bk == e.tile[2][0] && d.wm == e.tile[0][1] &&
-             d.wn == e.tile[1][1] && d.kg == e.tile[2][1] && usable(d, v, vec_ok, ws_ok);
-    };
-    auto vdist = [&](const InstanceDesc& d) {
-      return std::fabs(std::log2((double)d.vm) - std::log2((double)e.v[0])) +
-             std::fabs(std::log2((double)d.vn) - std::log2((double)e.v[1]));
-    };
-    double vmin = -1.0;
-    for (int i = 0; i < g_num_instances; ++i)
-      if (same_tiles(g_instances[i]) && (vmin < 0 || vdist(g_instances[i]) < vmin)) vmin = vdist(g_instances[i]);
+    // every compiled instance on the same spatial tiles (T_2 and T_1 of m and n) realises the
+    // state; its k tile, MFMA depth, V and staging mode are whatever was compiled
     for (int i = 0; i < g_num_instances; ++i) {
       const InstanceDesc& d = g_instances[i];
-      if (!same_tiles(d) || vdist(d) != vmin) continue;
+      if (d.bm != e.tile[0][0] || d.bn != e.tile[1][0] || d.wm != e.tile[0][1] || d.wn != e.tile[1][1]) continue;
+      if (!usable(d, v, vec_ok, ws_ok)) continue;
       const double us = predict_instance(v, c.hw, d);
       if (us > 0 && (!best || us < best_us)) { best = &d; best_us = us; }
     }
