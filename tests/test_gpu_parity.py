@@ -252,3 +252,59 @@ def test_error_paths_launch_nothing(gs):
     with pytest.raises(gs.GensorError) as e:
         gs.gemm(p, A, A, Cc, schedule=s)
     assert e.value.status == 3
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+def _full_size_case(gs, name):
+    """The benchmark workload `name` with the schedule bench.py would time (gensor_construct, seed 0)."""
+    import torch
+    w = inputs.all_configs()[name]
+    if isinstance(w, inputs.GemmWorkload):
+        p = gs.gemm_problem(w.dtype, w.M, w.N, w.K, w.transA, w.transB, w.batch)
+        s = gs.construct(p, seed=0)
+        out = gs.empty_device((w.batch, w.M, w.N) if w.batch > 1 else (w.M, w.N))
+        out.fill_(float("nan"))
+        dA, dB = gs.to_device(w.A, w.dtype), gs.to_device(w.B, w.dtype)
+        (gs.bmm if w.batch > 1 else gs.gemm)(p, dA, dB, out, 1.0, 0.0, s)
+        torch.cuda.synchronize()
+        co = inputs.sample_indices(21, (w.batch, w.M, w.N), 1500)
+        # whole first / last rows and columns as well: tile edges and the ragged last tile
+        edge = [(b, i, j) for b in (0, w.batch - 1) for i in (0, w.M - 1) for j in range(0, w.N, max(1, w.N // 97))]
+        edge += [(b, i, j) for b in (0, w.batch - 1) for j in (0, w.N - 1) for i in range(0, w.M, max(1, w.M // 97))]
+        co = np.concatenate([co, np.array(edge, dtype=np.int64)])
+        want = ops.bmm_at(w.A, w.B, w.dtype, co, transA=w.transA, transB=w.transB)
+        o3 = out if w.batch > 1 else out[None]
+        idx = torch.from_numpy(co).cuda()
+        got = o3[idx[:, 0], idx[:, 1], idx[:, 2]].double().cpu().numpy()
+        finite = bool(torch.isfinite(out).all())
+    else:
+        p = gs.conv_problem(w.dtype, w.n, w.c, w.h, w.w, w.k, w.r, w.s, w.stride, w.pad)
+        s = gs.construct(p, seed=0)
+        out = gs.empty_device((w.n, w.k, w.p, w.q))
+        out.fill_(float("nan"))
+        gs.conv2d(p, gs.to_device(w.I, w.dtype), gs.to_device(w.W, w.dtype), out, s, gs.conv_workspace(p, s))
+        torch.cuda.synchronize()
+        co = inputs.sample_indices(22, (w.n, w.k, w.p, w.q), 1500)
+        edge = [(n, k, p_, q_) for n in (0, w.n - 1) for k in (0, w.k - 1) for p_ in (0, w.p - 1) for q_ in range(w.q)]
+        edge += [(n, k, p_, q_) for n in (0, w.n - 1) for k in (0, w.k - 1) for q_ in (0, w.q - 1) for p_ in range(w.p)]
+        co = np.concatenate([co, np.array(edge, dtype=np.int64)])
+        want = ops.conv2d_at(w.I, w.W, w.dtype, co, stride=w.stride, pad=w.pad)
+        idx = torch.from_numpy(co).cuda()
+        got = out[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].double().cpu().numpy()
+        finite = bool(torch.isfinite(out).all())
+    return w, s, got, want, finite
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3_up", "cfg3_down", "cfg4", "cfg5_3x3", "cfg5_1x1s2"])
+def test_benchmark_shapes_full_size_sampled(gs, name):
+    """All five benchmark configurations at full size with the constructed schedule: sampled
+    entries plus tile-edge rows and columns against the oracle, every output finite (no entry
+    left unwritten), and the per-entry error within the fp32-accumulation bound."""
+    w, s, got, want, finite = _full_size_case(gs, name)
+    err = ops.rel_frobenius(got, want)
+    print(name, "kernel", s.kernel_id, "rel frobenius on samples", err)
+    assert finite
+    assert err <= TOL[w.dtype]
+    assert err <= 2e-6
+    scale = np.abs(want).max()
+    assert np.abs(got - want).max() <= 1e-4 * scale
