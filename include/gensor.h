@@ -181,6 +181,14 @@ gensor_status gensor_bmm(const gensor_schedule* s, const gensor_problem* p, floa
  * filters which the call first writes into `workspace` (device memory, 16-byte aligned,
  * at least gensor_workspace_bytes(s, p) bytes; GENSOR_ERR_WORKSPACE otherwise).  With
  * s == NULL such schedules are considered only if the workspace is large enough.
+ * A pointwise convolution (r = s = 1, pad = 0) is one GEMM per image, O[n] = W * X[n] with
+ * X[n][c][p*Q+q] = I[n][c][p*stride][q*stride]; gensor_construct and
+ * gensor_instance_schedule treat it as that batched GEMM (m = k filters, n = P*Q, k = c).
+ * With stride 1 the input itself is the B operand; with a larger stride the call first
+ * compacts the sampled input into `workspace` (n*c*P*Q elements, same size rule and error
+ * as above; with s == NULL and no such workspace the general implicit-GEMM path is used).
+ * The workspace is scratch: its contents after the call are unspecified and nothing is
+ * kept in it between calls.
  */
 gensor_status gensor_conv2d(const gensor_schedule* s, const gensor_problem* p,
                             const void* input, const void* weight, void* output,

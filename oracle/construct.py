@@ -53,6 +53,10 @@ Readings (the paper is silent or garbled here)
              n: the sizes Eq. 1's traffic depends on); k tile, MFMA depth, V and staging mode are
              then those of the instance.  The best such instance over all kept states wins (if
              none exists, the instance nearest to the best-ranked state)
+  views      a pointwise convolution (1x1 filter, no padding) is walked and ranked as the
+             batched GEMM it is (one GEMM per image, n-contiguous B); other convolutions in
+             the implicit-GEMM view.  Instances that cache the input patch in LDS have a
+             cost model of their own (predict_patch_us: a serial chain per workgroup)
 """
 from __future__ import annotations
 
@@ -86,6 +90,8 @@ class View:
     e: int = 2          # bytes per input element
     e_out: int = 4
     bsrc: int = 0       # 0 k-contiguous B, 1 n-contiguous B, 2 convolution gather
+    conv: Optional[Tuple[int, ...]] = None   # convolution geometry (n, c, h, w, r, s, stride, pad), else None
+    prepass: int = 0    # 1: a strided pointwise convolution (its input is compacted by a pre-pass kernel)
 
 
 @dataclass
@@ -375,9 +381,64 @@ class Instance:
     direct: int
 
 
+def predict_patch_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, stages) -> float:
+    """Patch-staged convolution: every workgroup runs a serial chain (first fetch, then per
+    channel stage: fetch issue, taps x MFMA, transpose + LDS commit, barriers; then the
+    stores); workgroups beyond the resident ones queue behind it."""
+    e, eo = view.e, view.e_out
+    n, c, h, w, r, s, stride, pad = view.conv
+    g = 16 if e == 2 else 8
+    mb = 32 if kg == g else 16
+    epc = 16 // e
+    P = (h + 2 * pad - r) // stride + 1
+    Qo = (w + 2 * pad - s) // stride + 1
+    RS = r * s
+    nst = math.ceil(c / bk)
+    out_rows = min(math.ceil((bn - 1) / Qo) + 1, n * P)
+    rows = (out_rows - 1) * stride + r + 2 * pad
+    pw = w + 2 * pad
+    stage = bm * (RS * bk * e + 16) + rows * pw * (bk * e + 16)
+    lds = stages * stage
+    if lds > hw.lds_bytes_per_cu:
+        return -1.0
+    nwaves = (bm // wm) * (bn // wn)
+    if nwaves > hw.max_waves_per_wg:
+        return -1.0
+    units = math.ceil(rows * math.ceil(w / epc) * (bk // epc) / (nwaves * 64))
+    avec = math.ceil(bm * RS * bk / epc / (nwaves * 64))
+    regs = wm * wn // 64 + (wm + wn) // 2 + 32 * units + 4 * avec + 48
+    if regs > hw.regs_per_lane:
+        return -1.0
+    occ = min(hw.lds_bytes_per_cu // lds, (hw.simds_per_cu * (hw.regs_per_lane // regs)) // nwaves, 8)
+    if occ < 1:
+        return -1.0
+    tiles = math.ceil(view.M / bm) * math.ceil(view.N / bn)
+    resident = min(occ, math.ceil(tiles / hw.compute_units))
+    rounds = max(1.0, tiles / (hw.compute_units * occ))
+    share = max(1.0, resident * nwaves / hw.simds_per_cu)
+    peak_simd = (hw.mfma_tflops_16bit if e == 2 else hw.mfma_tflops_f32) * 1e6 / (hw.compute_units * hw.simds_per_cu)
+    ksteps = bk // kg
+    t_mfma = RS * ksteps * (wm // mb) * (wn // mb) * (2.0 * mb * mb * kg) / peak_simd * share
+    lds_bw = hw.bandwidth_gbs[1] * 1e3 / hw.compute_units
+    t_lds = RS * ksteps * ((wm // mb) + (wn // mb)) * 1024.0 * nwaves / lds_bw * resident
+    l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units
+    t_feed = (rows * w * bk * e + bm * RS * bk * e) / l2_bw * resident
+    t_fixed = (hw.latency_ns[0] + 2.0 * hw.latency_ns[1]) * 1e-3            # fetch issue, commit, two barriers
+    t_stage = t_mfma + t_lds + t_feed + t_fixed
+    t_pro = (3.0 * hw.latency_ns[0] + 10.0 * hw.latency_ns[1]) * 1e-3       # index set-up, first fetch at full latency, zero fill
+    t_epi = bm * bn * eo / (0.6 * hw.bandwidth_gbs[0] * 1e3 / hw.compute_units)
+    t_cu = rounds * (t_pro + nst * t_stage + t_epi)
+    bytes_total = e * (n * c * h * w + view.M * view.K) + eo * view.M * view.N
+    t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3)
+    # the filter pre-pass is a dependent launch of its own
+    return max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + 3.5 * hw.launch_us
+
+
 def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, direct) -> float:
     """Analytical time of one launch: per-CU pipeline limits (MFMA, LDS, L2 feed) scaled by
     how many tiles the busiest CU owns, an epilogue that streams C, bounded below by HBM."""
+    if view.bsrc == 2 and direct and view.conv is not None:
+        return predict_patch_us(view, hw, bm, bn, bk, wm, wn, kg, stages)
     e, eo = view.e, view.e_out
     g = 16 if e == 2 else 8
     mb = 32 if kg == g else 16
@@ -420,7 +481,7 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     bytes_total = view.batch * (e * (view.M * view.K + view.K * view.N) + eo * view.M * view.N)
     t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3)
     # soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)
-    return max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + hw.launch_us
+    return max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + hw.launch_us * (3.5 if view.prepass else 1.0)
 
 
 def pick(view: View, hw: Hw, kept: Sequence[State], instances: Sequence[Instance], vec_ok: bool) -> Tuple[Optional[Instance], float, int]:

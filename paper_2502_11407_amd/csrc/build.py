@@ -15,6 +15,7 @@ import lattice  # noqa: E402
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", HERE,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",      # accumulators stay in plain VGPRs: no copies to and from AGPRs around loops
          "-Wno-unused-command-line-argument"]
 PER_TU = 4
 

@@ -262,9 +262,63 @@ int run_walk(const Ctx& c, uint64_t seed, uint64_t chain, std::vector<Etir>* kep
 // L2) scaled by how many tiles the busiest CU owns, an epilogue that streams C, bounded
 // below by total HBM traffic, plus launch cost.  Microseconds; negative = infeasible.
 // ---------------------------------------------------------------------------------------
+// Patch-staged convolution: every workgroup runs a serial chain (first fetch, then per channel
+// stage: fetch issue, taps x MFMA, transpose + LDS commit, barriers; then the stores);
+// workgroups beyond the resident ones queue behind it.
+double predict_patch(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, int wm, int wn, int kg, int stages) {
+  const int e = v.esize, eo = v.osize;
+  const int g = e == 2 ? 16 : 8;
+  const int mb = kg == g ? 32 : 16;
+  const int epc = 16 / e;
+  const int64_t RS = v.cr * v.cs;
+  const double nst = std::ceil((double)v.cc / bk);
+  double out_rows = std::ceil((double)(bn - 1) / (double)v.Q) + 1.0;
+  if (out_rows > (double)(v.cn * v.P)) out_rows = (double)(v.cn * v.P);
+  const int64_t rows = ((int64_t)out_rows - 1) * v.cstride + v.cr + 2 * v.cpad;
+  const int64_t pw = v.cw + 2 * v.cpad;
+  const int64_t stage = (int64_t)bm * (RS * bk * e + 16) + rows * pw * (bk * e + 16);
+  const int64_t lds = stages * stage;
+  if (lds > hw.lds_bytes_per_cu) return -1.0;
+  const int nwaves = (bm / wm) * (bn / wn);
+  if (nwaves > hw.max_waves_per_wg) return -1.0;
+  const int64_t units = (int64_t)std::ceil((double)(rows * (int64_t)std::ceil((double)v.cw / epc) * (bk / epc)) / (double)(nwaves * 64));
+  const int64_t avec = (int64_t)std::ceil((double)(bm * RS * bk) / epc / (double)(nwaves * 64));
+  const int64_t regs = wm * wn / 64 + (wm + wn) / 2 + 32 * units + 4 * avec + 48;
+  if (regs > hw.regs_per_lane) return -1.0;
+  int64_t occ = hw.lds_bytes_per_cu / lds;
+  const int64_t by_regs = (hw.simds_per_cu * (hw.regs_per_lane / regs)) / nwaves;
+  if (by_regs < occ) occ = by_regs;
+  if (occ > 8) occ = 8;
+  if (occ < 1) return -1.0;
+  const double tiles = std::ceil((double)v.M / bm) * std::ceil((double)v.N / bn);
+  const double cu_tiles = std::ceil(tiles / hw.compute_units);
+  const double resident = (double)occ < cu_tiles ? (double)occ : cu_tiles;
+  double rounds = tiles / (double)(hw.compute_units * occ);
+  if (rounds < 1.0) rounds = 1.0;
+  double share = resident * nwaves / hw.simds_per_cu;
+  if (share < 1.0) share = 1.0;
+  const double peak_simd = (e == 2 ? hw.mfma_tflops_16bit : hw.mfma_tflops_f32) * 1e6 / (double)(hw.compute_units * hw.simds_per_cu);
+  const int ksteps = bk / kg;
+  const double t_mfma = (double)(RS * ksteps * (wm / mb) * (wn / mb)) * (2.0 * mb * mb * kg) / peak_simd * share;
+  const double lds_bw = hw.bandwidth_gbs[1] * 1e3 / hw.compute_units;
+  const double t_lds = (double)(RS * ksteps * ((wm / mb) + (wn / mb))) * 1024.0 * nwaves / lds_bw * resident;
+  const double l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units;
+  const double t_feed = (double)(rows * v.cw * bk * e + bm * RS * bk * e) / l2_bw * resident;
+  const double t_fixed = (hw.latency_ns[0] + 2.0 * hw.latency_ns[1]) * 1e-3;
+  const double t_stage = t_mfma + t_lds + t_feed + t_fixed;
+  const double t_pro = (3.0 * hw.latency_ns[0] + 10.0 * hw.latency_ns[1]) * 1e-3;
+  const double t_epi = (double)(bm * bn * eo) / (0.6 * hw.bandwidth_gbs[0] * 1e3 / hw.compute_units);
+  const double t_cu = rounds * (t_pro + nst * t_stage + t_epi);
+  const double bytes_total = (double)(e * (v.cn * v.cc * v.ch * v.cw + v.M * v.K) + eo * v.M * v.N);
+  const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3);
+  // the filter pre-pass is a dependent launch of its own
+  return (t_cu > t_hbm ? t_cu : t_hbm) + 0.3 * (t_cu > t_hbm ? t_hbm : t_cu) + 3.5 * hw.launch_us;
+}
+
 double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, int wm, int wn, int kg,
                int vm, int vn, int vec, int stages, int direct) {
   (void)vm; (void)vn;
+  if (v.bsrc == B_CONV && direct) return predict_patch(v, hw, bm, bn, bk, wm, wn, kg, stages);
   const int e = v.esize, eo = v.osize;
   const int g = e == 2 ? 16 : 8;
   const int mb = kg == g ? 32 : 16;
@@ -310,7 +364,8 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   const double bytes_total = (double)v.batch * ((double)e * ((double)v.M * v.K + (double)v.K * v.N) + (double)eo * v.M * v.N);
   const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3);
   // soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)
-  return (t_cu > t_hbm ? t_cu : t_hbm) + 0.3 * (t_cu > t_hbm ? t_hbm : t_cu) + hw.launch_us;
+  const bool prepass = v.pointwise && v.cstride > 1;     // the input is compacted by a dependent launch of its own
+  return (t_cu > t_hbm ? t_cu : t_hbm) + 0.3 * (t_cu > t_hbm ? t_hbm : t_cu) + hw.launch_us * (prepass ? 3.5 : 1.0);
 }
 
 double predict_instance(const GemmView& v, const gensor_hw& hw, const InstanceDesc& d) {
@@ -328,11 +383,11 @@ bool usable(const InstanceDesc& d, const GemmView& v, bool vec_ok, bool ws_ok = 
 }  // namespace
 
 gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
-                                 uint64_t seed, bool vec_ok, bool ws_ok, gensor_schedule* out) {
+                                 uint64_t seed, bool vec_ok, bool ws_ok, bool allow_pointwise, gensor_schedule* out) {
   if (!p || !out) return GENSOR_ERR_INVALID_ARG;
   const auto t0 = std::chrono::steady_clock::now();
   GemmView v;
-  gensor_status st = gemm_view(p, &v);
+  gensor_status st = gemm_view(p, &v, allow_pointwise);
   if (st != GENSOR_OK) return st;
   Ctx c;
   make_ctx(v, hw, opts, &c);
@@ -401,7 +456,7 @@ extern "C" const gensor_hw* gensor_hw_mi355x(void) { return &kMi355x; }
 
 extern "C" gensor_status gensor_construct(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
                                           uint64_t seed, gensor_schedule* out) {
-  return construct_internal(p, hw, opts, seed, true, true, out);
+  return construct_internal(p, hw, opts, seed, true, true, true, out);
 }
 
 extern "C" gensor_status gensor_construct_trace(const gensor_problem* p, const gensor_hw* hw,

@@ -23,7 +23,7 @@
 
 namespace gensor {
 
-template <typename T_, typename OutT_, int BM_, int BN_, int BKC_, int WM_, int WN_, int MB_, int UNITS_>
+template <typename T_, typename OutT_, int BM_, int BN_, int BKC_, int WM_, int WN_, int MB_, int UNITS_, int LSTAGES_>
 struct ConvCfg {
   typedef T_ T;
   typedef OutT_ OutT;
@@ -41,6 +41,8 @@ struct ConvCfg {
   static constexpr int RS_MAX = 9;                     // taps supported by the staging registers
   static constexpr int A_VEC_MAX = (BM * BKC * RS_MAX / EPC + THREADS - 1) / THREADS;
   static constexpr int UNITS_MAX = UNITS_;             // patch transpose units per thread and stage
+  static constexpr int LSTAGES = LSTAGES_;             // LDS buffers: 1 or 2
+  static_assert(LSTAGES == 1 || LSTAGES == 2, "one or two LDS stages");
   static_assert(BKC % KG == 0 && KSTEPS_C >= 1, "channel tile must hold whole fragment k groups");
   static_assert(BM % WM == 0 && BN % WN == 0 && WM % MB == 0 && WN % MB == 0, "tiles");
 };
@@ -58,6 +60,64 @@ __global__ __launch_bounds__(256) void permute_filters(const void* w, void* out,
   const int64_t src = (k * Cc + c) * RS + rs;
   if constexpr (ES == 4) ((uint32_t*)out)[i] = ((const uint32_t*)w)[src];
   else ((uint16_t*)out)[i] = ((const uint16_t*)w)[src];
+}
+
+// Input of a strided pointwise convolution, compacted: out[plane][p][q] = in[plane][p*stride][q*stride]
+// for plane = (image, channel).  16 / ES consecutive outputs per thread, one 16-byte store.
+template <int ES>
+__global__ __launch_bounds__(256) void subsample_input(const void* in, void* out, int64_t planes, int H, int W, int P, int Q,
+                                                       int stride) {
+  constexpr int EPC = 16 / ES;
+  const int64_t PQ = (int64_t)P * Q;
+  const int64_t total = planes * PQ;
+  const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * EPC;
+  if (i0 >= total) return;
+  int64_t plane = i0 / PQ;
+  int rem = (int)(i0 - plane * PQ);
+  int p = rem / Q, q = rem - p * Q;
+  u32x4 v = {0u, 0u, 0u, 0u};
+  const int count = (int)(total - i0 < EPC ? total - i0 : EPC);
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) {
+    if (e < count) {
+      const int64_t src = (plane * H + (int64_t)p * stride) * W + (int64_t)q * stride;
+      if constexpr (ES == 4) v[e] = ((const uint32_t*)in)[src];
+      else v[e >> 1] |= (uint32_t)((const uint16_t*)in)[src] << ((e & 1) * 16);
+      if (++q == Q) { q = 0; if (++p == P) { p = 0; ++plane; } }
+    }
+  }
+  if (count == EPC) {
+    *(u32x4*)((char*)out + i0 * ES) = v;
+  } else {
+    for (int e = 0; e < count; ++e) {
+      if constexpr (ES == 4) ((uint32_t*)out)[i0 + e] = v[e];
+      else ((uint16_t*)out)[i0 + e] = (uint16_t)(v[e >> 1] >> ((e & 1) * 16));
+    }
+  }
+}
+
+// The same for stride 2 when W is a whole number of 16-byte vectors (so Q = W / 2 and every
+// output row is a whole number of half vectors): one 16-byte load, every other element kept,
+// one 8-byte store per thread.  groups = planes * P * Q / (EPC / 2) must fit 31 bits.
+template <int ES>
+__global__ __launch_bounds__(256) void subsample2_input(const void* in, void* out, int groups, int H, int W, int P, int Q) {
+  constexpr int EPC = 16 / ES, HALF = EPC / 2;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= groups) return;
+  const int qg = Q / HALF;
+  const int row = t / qg, g = t - row * qg;          // row = plane * P + p
+  const int plane = row / P, p = row - plane * P;
+  const int64_t src = ((int64_t)plane * H + 2 * p) * W + g * EPC;
+  const u32x4 v = *(const u32x4*)((const char*)in + src * ES);
+  uint32_t o0, o1;
+  if constexpr (ES == 4) {
+    o0 = v[0]; o1 = v[2];
+  } else {
+    o0 = __builtin_amdgcn_perm(v[1], v[0], 0x05040100u);
+    o1 = __builtin_amdgcn_perm(v[3], v[2], 0x05040100u);
+  }
+  uint2 o = {o0, o1};
+  *(uint2*)((char*)out + (int64_t)t * 8) = o;
 }
 
 template <typename C>
@@ -168,6 +228,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
     u_dst[u] = (j * PW + pad + seg * EPC) * SLOT + oct * 16;
     u_nx[u] = min(EPC, W - seg * EPC);
   }
+  const bool tail_check = (W % EPC) != 0;          // only then can a vector run past the end of the tensor
   auto fetch_patch = [&](int c0) {
 #pragma unroll
     for (int u = 0; u < C::UNITS_MAX; ++u) {
@@ -177,7 +238,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
 #pragma unroll
       for (int i = 0; i < EPC; ++i) {
         const uint32_t off = ok ? (uint32_t)((u_goff[u] + (c0 + i) * HW) * ES) : OOB;
-        if (ok && off + 16u > (uint32_t)args.cInBytes) {
+        if (tail_check && ok && off + 16u > (uint32_t)args.cInBytes) {
           // the very last vector of the tensor: a 16-byte read would leave the buffer, which
           // drops the valid part when the start is not dword aligned; fetch element-wise
           u32x4 v = {0u, 0u, 0u, 0u};
@@ -231,40 +292,68 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
     const int img = g / P, p = g - img * P;
     b_base[bj] = ((img * Hp + p * stride - R0) * PW + q * stride) * SLOT;
   }
+  // One tap = KSTEPS_C fragment reads per block and the MFMAs on them.  The taps run as a
+  // flat loop, two per trip, with the fragments of the next tap in flight under the MFMAs
+  // of this one (two register sets).
+  u32x4 af[2][C::KSTEPS_C][C::MBLK], bf[2][C::KSTEPS_C][C::NBLK];
   auto compute = [&](int st) {
     GENSOR_LDS char* abase = lds + st * stage_bytes;
     GENSOR_LDS char* pbase = abase + a_bytes;
-    for (int r = 0; r < R; ++r)
-      for (int s = 0; s < S; ++s) {
-        const int tap = (r * PW + s) * SLOT;
-        const int rs = r * S + s;
+    auto read_tap = [&](int buf, int r, int s2) {
+      const int tap = (r * PW + s2) * SLOT;
+      const int rs = r * S + s2;
 #pragma unroll
-        for (int ks = 0; ks < C::KSTEPS_C; ++ks) {
-          const int ch = ks * C::LANE_GROUPS + fgrp;
-          u32x4 af[C::MBLK], bf[C::NBLK];
+      for (int ks = 0; ks < C::KSTEPS_C; ++ks) {
+        const int ch = ks * C::LANE_GROUPS + fgrp;
 #pragma unroll
-          for (int bi = 0; bi < C::MBLK; ++bi)
-            af[bi] = *(GENSOR_LDS u32x4*)(abase + (block_row(bi) + frow) * a_pitch + (rs * C::OCT + ch) * 16);
+        for (int bi = 0; bi < C::MBLK; ++bi)
+          af[buf][ks][bi] = *(GENSOR_LDS u32x4*)(abase + (block_row(bi) + frow) * a_pitch + (rs * C::OCT + ch) * 16);
 #pragma unroll
-          for (int bj = 0; bj < C::NBLK; ++bj) bf[bj] = *(GENSOR_LDS u32x4*)(pbase + b_base[bj] + tap + ch * 16);
-#pragma unroll
-          for (int bi = 0; bi < C::MBLK; ++bi)
-#pragma unroll
-            for (int bj = 0; bj < C::NBLK; ++bj) MF::run(af[bi], bf[bj], acc[bi][bj]);
-        }
+        for (int bj = 0; bj < C::NBLK; ++bj) bf[buf][ks][bj] = *(GENSOR_LDS u32x4*)(pbase + b_base[bj] + tap + ch * 16);
       }
+    };
+    auto mma_tap = [&](int buf) {
+#pragma unroll
+      for (int ks = 0; ks < C::KSTEPS_C; ++ks)
+#pragma unroll
+        for (int bi = 0; bi < C::MBLK; ++bi)
+#pragma unroll
+          for (int bj = 0; bj < C::NBLK; ++bj) MF::run(af[buf][ks][bi], bf[buf][ks][bj], acc[bi][bj]);
+    };
+    int r = 0, s2 = 0;                                  // the next tap to read
+    auto advance = [&]() { if (++s2 == S) { s2 = 0; ++r; } };
+    read_tap(0, 0, 0);
+    advance();
+    // branch-free body: two taps per trip; the last one or two taps are peeled off
+    const int pairs = (RS - 1) >> 1;
+    for (int i = 0; i < pairs; ++i) {
+      read_tap(1, r, s2);
+      advance();
+      mma_tap(0);
+      read_tap(0, r, s2);
+      advance();
+      mma_tap(1);
+    }
+    if (RS - 2 * pairs == 2) {
+      read_tap(1, r, s2);
+      mma_tap(0);
+      mma_tap(1);
+    } else {
+      mma_tap(0);
+    }
   };
 
-  // ---- zero both patch buffers once: cells outside the images are never written again
-  {
-    const u32x4 z = {0u, 0u, 0u, 0u};
-    const int patch_bytes = stage_bytes - a_bytes;
-    for (int st = 0; st < 2; ++st)
-      for (int o = tid * 16; o < patch_bytes; o += C::THREADS * 16) *(GENSOR_LDS u32x4*)(lds + st * stage_bytes + a_bytes + o) = z;
-  }
   const int nstages = (Cc + BKC - 1) / BKC;
   fetch_a(0);
   fetch_patch(0);
+  // ---- zero the patch buffers once (under the first loads): cells outside the images are
+  // never written again
+  {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    const int patch_bytes = stage_bytes - a_bytes;
+    for (int st = 0; st < C::LSTAGES; ++st)
+      for (int o = tid * 16; o < patch_bytes; o += C::THREADS * 16) *(GENSOR_LDS u32x4*)(lds + st * stage_bytes + a_bytes + o) = z;
+  }
   __syncthreads();
   commit_a(0);
   commit_patch(0);
@@ -275,10 +364,21 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
       fetch_a((st + 1) * BKC);
       fetch_patch((st + 1) * BKC);
     }
-    compute(st & 1);
-    if (more) {
-      commit_a((st + 1) & 1);
-      commit_patch((st + 1) & 1);
+    if constexpr (C::LSTAGES == 2) {
+      compute(st & 1);
+      if (more) {
+        commit_a((st + 1) & 1);
+        commit_patch((st + 1) & 1);
+      }
+    } else {
+      // one buffer: every wave must have read this stage before the next one overwrites it;
+      // other workgroups on the CU fill the gap
+      compute(0);
+      if (more) {
+        __syncthreads();
+        commit_a(0);
+        commit_patch(0);
+      }
     }
     __syncthreads();
   }

@@ -31,7 +31,7 @@ namespace gensor {
 
 static bool valid_dtype(int d) { return d == GENSOR_F32 || d == GENSOR_F16 || d == GENSOR_BF16; }
 
-gensor_status gemm_view(const gensor_problem* p, GemmView* v) {
+gensor_status gemm_view(const gensor_problem* p, GemmView* v, bool allow_pointwise) {
   if (!p || !v) return GENSOR_ERR_INVALID_ARG;
   if (!valid_dtype(p->in_dtype) || !valid_dtype(p->out_dtype)) return GENSOR_ERR_INVALID_ARG;
   if (p->out_dtype != GENSOR_F32 && p->out_dtype != p->in_dtype) return GENSOR_ERR_UNSUPPORTED;
@@ -61,6 +61,13 @@ gensor_status gemm_view(const gensor_problem* p, GemmView* v) {
     v->bsrc = B_CONV;
     v->cn = p->n; v->cc = p->c; v->ch = p->h; v->cw = p->w; v->cr = p->r; v->cs = p->s;
     v->cstride = p->stride; v->cpad = p->pad;
+    if (allow_pointwise && p->r == 1 && p->s == 1 && p->pad == 0) {
+      v->pointwise = 1;
+      v->N = v->P * v->Q;
+      v->K = p->c;
+      v->batch = p->n;
+      v->bsrc = B_NC;
+    }
   } else {
     return GENSOR_ERR_INVALID_ARG;
   }
@@ -112,7 +119,7 @@ bool conv_patch_plan(const InstanceDesc& d, const GemmView& v, ConvPlan* plan) {
   pl.patch_rows = (int)rows;
   const int slot = d.bk * v.esize + 16;
   const int64_t stage = (int64_t)d.bm * pl.a_pitch + rows * pw * slot;
-  if (2 * stage > 160 * 1024) return false;
+  if (d.stages * stage > 160 * 1024) return false;
   pl.stage_bytes = (int)stage;
   const int64_t units = rows * ((v.cw + epc - 1) / epc) * (d.bk / epc);
   if (units > (int64_t)d.units * d.threads) return false;
@@ -167,15 +174,25 @@ extern "C" gensor_status gensor_instance_schedule(int32_t id, const gensor_probl
   return GENSOR_OK;
 }
 
+namespace gensor {
+// Bytes of the compacted input of a strided pointwise convolution (0: the input is used as it is).
+static size_t pointwise_workspace(const GemmView& v) {
+  return v.pointwise && v.cstride > 1 ? (size_t)(v.batch * v.K * v.N * v.esize) : 0;
+}
+}  // namespace gensor
+
 // Patch-staged convolution instances read a K,R,S,C copy of the filters that the library
-// writes into the caller's workspace; nothing else needs one.
+// writes into the caller's workspace; a strided pointwise convolution run as a batched GEMM
+// reads a compacted copy of the input from it; nothing else needs one.
 extern "C" size_t gensor_workspace_bytes(const gensor_schedule* s, const gensor_problem* p) {
-  GemmView v;
-  if (!p || gemm_view(p, &v) != GENSOR_OK || v.bsrc != B_CONV) return 0;
-  const size_t need = (size_t)(v.M * v.K * v.esize);
-  if (!s) return need;                       // what any schedule the library may construct can ask for
-  const InstanceDesc* d = find_instance(s, v);
-  return d && d->units ? need : 0;
+  GemmView v, g;
+  if (!p || p->op != GENSOR_OP_CONV2D || gemm_view(p, &v) != GENSOR_OK || gemm_view(p, &g, false) != GENSOR_OK) return 0;
+  const size_t need_patch = (size_t)(g.M * g.K * g.esize);
+  const size_t need_pw = pointwise_workspace(v);
+  if (!s) return need_patch > need_pw ? need_patch : need_pw;   // what any schedule the library may construct can ask for
+  if (v.pointwise && find_instance(s, v)) return need_pw;
+  const InstanceDesc* d = find_instance(s, g);
+  return d && d->units ? need_patch : 0;
 }
 
 // ------------------------------------------------------------------------------------
@@ -185,8 +202,9 @@ namespace {
 std::mutex g_memo_mutex;
 std::map<std::tuple<int, int, int, int, int, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int>, gensor_schedule> g_memo;
 
-gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, bool ws_ok, gensor_schedule* out) {
-  auto key = std::make_tuple((int)p->op, (int)p->in_dtype, (int)p->out_dtype, (int)p->transB, (vec_ok ? 1 : 0) + (ws_ok ? 2 : 0),
+gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, bool ws_ok, bool pointwise, gensor_schedule* out) {
+  auto key = std::make_tuple((int)p->op, (int)p->in_dtype, (int)p->out_dtype, (int)p->transB,
+                             (vec_ok ? 1 : 0) + (ws_ok ? 2 : 0) + (pointwise ? 4 : 0),
                              p->op == GENSOR_OP_CONV2D ? p->n : p->batch, p->op == GENSOR_OP_CONV2D ? p->c : p->M,
                              p->op == GENSOR_OP_CONV2D ? p->h : p->N, p->op == GENSOR_OP_CONV2D ? p->w : p->K,
                              p->op == GENSOR_OP_CONV2D ? p->k : 0, p->op == GENSOR_OP_CONV2D ? p->r : 0,
@@ -195,7 +213,7 @@ gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, bool ws_ok
   std::lock_guard<std::mutex> lock(g_memo_mutex);
   auto it = g_memo.find(key);
   if (it != g_memo.end()) { *out = it->second; return GENSOR_OK; }
-  gensor_status st = construct_internal(p, nullptr, nullptr, 0, vec_ok, ws_ok, out);
+  gensor_status st = construct_internal(p, nullptr, nullptr, 0, vec_ok, ws_ok, pointwise, out);
   if (st == GENSOR_OK) g_memo[key] = *out;
   return st;
 }
@@ -208,7 +226,7 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
                      workspace_bytes >= (size_t)(v.M * v.K * v.esize);
   gensor_schedule local;
   if (!s) {
-    gensor_status st = memoised_schedule(p, vec_ok, ws_ok, &local);
+    gensor_status st = memoised_schedule(p, vec_ok, ws_ok, v.pointwise != 0, &local);
     if (st != GENSOR_OK) return st;
     s = &local;
   }
@@ -287,7 +305,54 @@ extern "C" gensor_status gensor_conv2d(const gensor_schedule* s, const gensor_pr
   GemmView v;
   gensor_status st = gemm_view(p, &v);
   if (st != GENSOR_OK) return st;
-  if (p->n * p->c * p->h * p->w > INT32_MAX) { /* index arithmetic of the gather is 64-bit; extents are 32-bit */ }
+  if (v.pointwise) {
+    // one GEMM per image: A = filters [k][c] shared by all images, B = the (sampled) input
+    // [c][P*Q] of the image, C = its output [k][P*Q].  An explicit schedule may instead name
+    // an instance of the general view; without the workspace a strided input needs, a NULL
+    // schedule falls back to the general view as well.
+    const size_t need = pointwise_workspace(v);
+    const bool have = need == 0 || (workspace && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0 && workspace_bytes >= need);
+    bool use = have;
+    if (s) {
+      if (find_instance(s, v)) { if (!have) return GENSOR_ERR_WORKSPACE; }
+      else use = false;
+    }
+    if (use) {
+      const void* X = input;
+      const int64_t PQ = v.N;
+      if (need) {
+        const int64_t planes = p->n * p->c;
+        const int epc = 16 / v.esize;
+        hipStream_t stream = (hipStream_t)hip_stream;
+        const int64_t groups = planes * PQ / (epc / 2);
+        if (p->stride == 2 && p->w % epc == 0 && (reinterpret_cast<uintptr_t>(input) & 15u) == 0 && groups < INT32_MAX) {
+          const unsigned blocks = (unsigned)((groups + 255) / 256);
+          if (v.esize == 4)
+            hipLaunchKernelGGL(subsample2_input<4>, dim3(blocks), dim3(256), 0, stream, input, workspace, (int)groups,
+                               (int)p->h, (int)p->w, (int)v.P, (int)v.Q);
+          else
+            hipLaunchKernelGGL(subsample2_input<2>, dim3(blocks), dim3(256), 0, stream, input, workspace, (int)groups,
+                               (int)p->h, (int)p->w, (int)v.P, (int)v.Q);
+        } else {
+          const int64_t threads = (planes * PQ + epc - 1) / epc;
+          if ((threads + 255) / 256 > INT32_MAX) return GENSOR_ERR_UNSUPPORTED;
+          const unsigned blocks = (unsigned)((threads + 255) / 256);
+          if (v.esize == 4)
+            hipLaunchKernelGGL(subsample_input<4>, dim3(blocks), dim3(256), 0, stream, input, workspace, planes,
+                               (int)p->h, (int)p->w, (int)v.P, (int)v.Q, (int)p->stride);
+          else
+            hipLaunchKernelGGL(subsample_input<2>, dim3(blocks), dim3(256), 0, stream, input, workspace, planes,
+                               (int)p->h, (int)p->w, (int)v.P, (int)v.Q, (int)p->stride);
+        }
+        if (hipGetLastError() != hipSuccess) return GENSOR_ERR_DEVICE;
+        X = workspace;
+      }
+      const int64_t ldb = need ? PQ : p->h * p->w;
+      return run(s, p, v, 1.0f, weight, v.K, 0, X, ldb, v.K * ldb, 0.0f, output, PQ, v.M * PQ, nullptr, 0, hip_stream);
+    }
+    st = gemm_view(p, &v, false);
+    if (st != GENSOR_OK) return st;
+  }
   // A = filters [k][c*r*s] (k-contiguous), B = gathered input, C = output viewed per image.
   return run(s, p, v, 1.0f, weight, v.K, 0, input, 0, 0, 0.0f, output, v.N, 0, workspace, workspace_bytes, hip_stream);
 }

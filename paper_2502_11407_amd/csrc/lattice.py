@@ -13,9 +13,11 @@ def _inst(dt, out, bm, bn, bk, wm, wn, mb, vm=1, vn=1, bsrc="KC", vec=1, stages=
                 bsrc=bsrc, vec=vec, stages=stages, direct=direct, units=units)
 
 
-def _convp(dt, out, bm, bn, bkc, wm, wn, units):
-    """Convolution with the input patch staged in LDS (direct = 1 on the CONV source); bk = channels per stage."""
-    return _inst(dt, out, bm, bn, bkc, wm, wn, 32, 1, 1, "CONV", 1, 2, 1, units)
+def _convp(dt, out, bm, bn, bkc, wm, wn, units, stages=2):
+    """Convolution with the input patch staged in LDS (direct = 1 on the CONV source); bk = channels per stage;
+    stages = LDS buffers (1: more workgroups per CU hide the load latency, 2: the next stage is written while
+    this one is multiplied)."""
+    return _inst(dt, out, bm, bn, bkc, wm, wn, 32, 1, 1, "CONV", 1, stages, 1, units)
 
 
 def lattice():
@@ -65,6 +67,9 @@ def lattice():
                                              (128, 128, 16, 64, 64, 1), (128, 256, 16, 64, 64, 1), (256, 128, 16, 64, 64, 1),
                                              (32, 256, 16, 32, 64, 1), (64, 256, 16, 64, 64, 2), (128, 128, 16, 64, 64, 2)]:
             out.append(_convp(dt, "f32", bm, bn, bkc, wm, wn, units))
+        for (bm, bn, bkc, wm, wn, units) in [(64, 256, 16, 64, 64, 1), (64, 128, 16, 32, 64, 1), (64, 64, 16, 32, 32, 1),
+                                             (32, 256, 16, 32, 64, 1), (32, 128, 16, 32, 32, 1), (64, 256, 16, 32, 64, 1)]:
+            out.append(_convp(dt, "f32", bm, bn, bkc, wm, wn, units, stages=1))
         out.append(_convp(dt, dt, 64, 128, 16, 32, 64, 1))
     for (bm, bn, bkc, wm, wn, units) in [(64, 128, 8, 32, 64, 1), (64, 64, 8, 32, 32, 1), (128, 128, 8, 64, 64, 2)]:
         out.append(_convp("f32", "f32", bm, bn, bkc, wm, wn, units))
@@ -87,8 +92,8 @@ def lattice():
 
 def cfg_type(d):
     if d["units"]:
-        return "ConvCfg<%s, %s, %d, %d, %d, %d, %d, %d, %d>" % (
-            CT[d["dt"]], CT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"], d["units"])
+        return "ConvCfg<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d>" % (
+            CT[d["dt"]], CT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"], d["units"], d["stages"])
     return ("Cfg<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s, %d, %s>" % (
         CT[d["dt"]], CT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"], d["vm"], d["vn"],
         BSRC[d["bsrc"]], "true" if d["vec"] else "false", d["stages"], "true" if d["direct"] else "false"))

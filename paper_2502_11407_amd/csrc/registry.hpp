@@ -36,7 +36,7 @@ hipError_t launch_instance(const KernelArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-// patch-staged convolution: the LDS size depends on the problem (a.cStageBytes, two stages).
+// patch-staged convolution: the LDS size depends on the problem (a.cStageBytes per LDS stage).
 // a.A is the caller's KCRS filter tensor and a.cWorkspace receives its K,R,S,C copy.
 template <typename C>
 hipError_t launch_conv_instance(const KernelArgs& a0, hipStream_t st) {
@@ -57,7 +57,7 @@ hipError_t launch_conv_instance(const KernelArgs& a0, hipStream_t st) {
     configured = true;
   }
   const unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n;
-  hipLaunchKernelGGL(conv_patch_kernel<C>, dim3(grid), dim3(C::THREADS), 2 * a.cStageBytes, st, a);
+  hipLaunchKernelGGL(conv_patch_kernel<C>, dim3(grid), dim3(C::THREADS), C::LSTAGES * a.cStageBytes, st, a);
   return hipGetLastError();
 }
 

@@ -258,8 +258,15 @@ def _views():
         (gs.gemm_problem("f32", 512, 512, 512, 0, 0), oc.View(512, 512, 512, 1, 4, 4, 1)),
         (gs.gemm_problem("f16", 8192, 3072, 768, 0, 0), oc.View(8192, 3072, 768, 1, 2, 4, 1)),
         (gs.gemm_problem("bf16", 1024, 1024, 64, 0, 1, 96), oc.View(1024, 1024, 64, 96, 2, 4, 0)),
-        (gs.conv_problem("f16", 32, 64, 56, 56, 64, 3, 3, 1, 1), oc.View(64, 32 * 56 * 56, 576, 1, 2, 4, 2)),
-        (gs.conv_problem("f16", 32, 256, 56, 56, 512, 1, 1, 2, 0), oc.View(512, 32 * 28 * 28, 256, 1, 2, 4, 2)),
+        (gs.conv_problem("f16", 32, 64, 56, 56, 64, 3, 3, 1, 1),
+         oc.View(64, 32 * 56 * 56, 576, 1, 2, 4, 2, conv=(32, 64, 56, 56, 3, 3, 1, 1))),
+        # pointwise convolution (1x1, no padding): one GEMM per image with an n-contiguous B
+        (gs.conv_problem("f16", 32, 256, 56, 56, 512, 1, 1, 2, 0),
+         oc.View(512, 28 * 28, 256, 32, 2, 4, 1, conv=(32, 256, 56, 56, 1, 1, 2, 0), prepass=1)),
+        (gs.conv_problem("f16", 32, 256, 56, 56, 512, 1, 1, 2, 1),
+         oc.View(512, 32 * 29 * 29, 256, 1, 2, 4, 2, conv=(32, 256, 56, 56, 1, 1, 2, 1))),
+        (gs.conv_problem("f32", 4, 24, 13, 11, 40, 3, 2, 2, 1),
+         oc.View(40, 4 * 7 * 6, 24 * 6, 1, 4, 4, 2, conv=(4, 24, 13, 11, 3, 2, 2, 1))),
         (gs.gemm_problem("f16", 65536, 1024, 4, 0, 0), oc.View(65536, 1024, 4, 1, 2, 4, 1)),
         (gs.gemm_problem("f16", 77, 53, 41, 0, 0, 1, "f16"), oc.View(77, 53, 41, 1, 2, 2, 1)),
     ]

@@ -179,7 +179,7 @@ def test_conv_geometry_bit_exact(gs, stride, pad, r, s):
     # n, c, h, w, k, r, s, stride, pad
     (3, 24, 13, 11, 70, 3, 3, 1, 1),     # channel tail (24 = 16 + 8), W not a multiple of 8, tiles span images
     (2, 16, 9, 20, 33, 3, 3, 2, 1),      # stride 2
-    (2, 40, 12, 12, 64, 1, 1, 2, 0),     # 1x1 stride 2, no padding
+    (2, 40, 12, 12, 64, 1, 1, 2, 1),     # 1x1 stride 2 (with padding: without it the problem is a batched GEMM)
     (1, 8, 7, 30, 16, 1, 3, 1, 2),       # 1x3 filter, padding wider than the filter needs
     (4, 32, 6, 6, 130, 3, 3, 1, 0),      # valid convolution, tiny images: a tile covers several images
     (2, 16, 16, 16, 64, 2, 2, 1, 1),     # even filter
@@ -207,6 +207,54 @@ def test_conv_patch_instances_bit_exact(gs, dtype, geom):
         assert np.array_equal(got, want), f"instance {idx}: max abs diff {np.nanmax(np.abs(got - want))}"
         ran += 1
     assert ran >= 2
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("geom", [
+    # n, c, h, w, k, stride
+    (3, 40, 12, 16, 70, 1),      # the input itself is the B operand (ldb = H*W)
+    (3, 40, 12, 16, 70, 2),      # compacted through the workspace; P*Q = 48
+    (2, 24, 13, 11, 33, 3),      # P*Q = 20: not a whole number of 16-byte chunks, scalar instances only
+    (2, 16, 31, 31, 16, 2),      # P*Q = 256, several n tiles
+])
+def test_pointwise_conv_is_a_batched_gemm(gs, dtype, geom):
+    """1x1 filter, no padding: every n-contiguous-B GEMM instance that serves the per-image view,
+    bit-exact on integers; then the default schedule with and without the workspace."""
+    import torch
+    n, c, h, w, k, stride = geom
+    I = inputs.small_ints(21, (n, c, h, w), dtype, -2, 2)
+    W = inputs.small_ints(22, (k, c, 1, 1), dtype, -2, 2)
+    want = ops.conv2d(I, W, dtype, stride=stride, pad=0)
+    p = gs.conv_problem(dtype, n, c, h, w, k, 1, 1, stride, 0)
+    dI, dW = gs.to_device(I, dtype), gs.to_device(W, dtype)
+    pq = want.shape[2] * want.shape[3]
+    esize = 4 if dtype == "f32" else 2
+    assert gs.workspace_bytes(p) >= (n * c * pq * esize if stride > 1 else 0)
+    ran = 0
+    for idx in range(gs.num_instances()):
+        sch = gs.instance_schedule(idx, p)
+        if sch is None or (sch.vec_bytes == 16 and pq % (16 // esize)):
+            continue
+        assert gs.workspace_bytes(p, sch) == (n * c * pq * esize if stride > 1 else 0)
+        print(f"pointwise conv instance {idx} tile {sch.tile[0][0]}x{sch.tile[1][0]}x{sch.tile[2][0]} geom {geom} {dtype}", flush=True)
+        dO = gs.empty_device(want.shape)
+        dO.fill_(float("nan"))
+        gs.conv2d(p, dI, dW, dO, sch, gs.conv_workspace(p, sch))
+        torch.cuda.synchronize()
+        got = gs.to_host_f64(dO)
+        assert np.array_equal(got, want), f"instance {idx}: max abs diff {np.nanmax(np.abs(got - want))}"
+        if stride > 1:
+            with pytest.raises(gs.GensorError) as e:
+                gs.conv2d(p, dI, dW, dO, sch)               # the schedule needs the compacted input
+            assert e.value.status == 4
+        ran += 1
+    assert ran >= (1 if pq % (16 // esize) else 2)
+    for ws in (gs.conv_workspace(p), None):                  # None: strided input falls back to the general view
+        dO = gs.empty_device(want.shape)
+        dO.fill_(float("nan"))
+        gs.conv2d(p, dI, dW, dO, None, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(gs.to_host_f64(dO), want)
 
 
 def test_conv_without_workspace(gs):
