@@ -9,8 +9,11 @@ gensor_construct picked for it; inputs are resident in HBM before the timed regi
                 stream the kernel runs on)
   cpu_baseline  the CPU oracle timed on a bounded slice of the same GEMM
   operators     every other benchmark shape (fp32 GEMM, GPT-2 GEMMs, attention-score
-                BMM, ResNet-50 convolutions) timed the same way, with schedule-construction
-                wall time and a sampled parity error against the oracle
+                BMM, ResNet-50 convolutions) timed the same way (median of 5 batches), with
+                the fraction of its own roofline ceiling min(MFMA peak, flop/byte x HBM
+                peak), a cold-cache time (operand sets rotated through more than the 256 MB
+                Infinity Cache), schedule-construction wall time and a sampled parity error
+                against the oracle
 """
 import argparse
 import json
@@ -38,6 +41,9 @@ def _algorithmic_bytes(w, gs_inputs):
     return es * (w.n * w.c * w.h * w.w + w.k * w.c * w.r * w.s) + 4 * w.n * w.k * w.p * w.q
 
 
+COLD_BYTES = 640 << 20     # operand sets rotated through in the cold-cache timing (Infinity Cache: 256 MB)
+
+
 class Case:
     """One workload resident on the device with its constructed schedule."""
 
@@ -57,16 +63,55 @@ class Case:
         self.sched = gs.construct(self.p, seed=0)
         self.construct_s = time.perf_counter() - t0
         self.ws = None if self.is_gemm else gs.conv_workspace(self.p, self.sched)
+        self.sets = [(self.a, self.b, self.out)]
         torch.cuda.synchronize()
 
-    def launch(self):
+    def launch(self, which=0):
         gs, w = self.gs, self.w
+        a, b, out = self.sets[which]
         if not self.is_gemm:
-            gs.conv2d(self.p, self.a, self.b, self.out, self.sched, self.ws)
+            gs.conv2d(self.p, a, b, out, self.sched, self.ws)
         elif w.batch > 1:
-            gs.bmm(self.p, self.a, self.b, self.out, 1.0, 0.0, self.sched)
+            gs.bmm(self.p, a, b, out, 1.0, 0.0, self.sched)
         else:
-            gs.gemm(self.p, self.a, self.b, self.out, 1.0, 0.0, self.sched)
+            gs.gemm(self.p, a, b, out, 1.0, 0.0, self.sched)
+
+    def time_cold_ms(self, launches=20):
+        """Average launch duration when every launch works on another copy of the operands, the
+        copies together larger than the Infinity Cache, so inputs come from HBM."""
+        import torch
+        per_set = sum(t.numel() * t.element_size() for t in self.sets[0])
+        n_sets = max(2, -(-COLD_BYTES // per_set))
+        while len(self.sets) < n_sets:
+            self.sets.append((self.a.clone(), self.b.clone(), torch.empty_like(self.out)))
+        for i in range(n_sets):
+            self.launch(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(launches):
+            self.launch(i % n_sets)
+        e1.record()
+        torch.cuda.synchronize()
+        del self.sets[1:]
+        return e0.elapsed_time(e1) / launches, n_sets
+
+    def time_median_ms(self, steps, warmup, batches=5):
+        """Median over `batches` event-bracketed batches of `steps` launches."""
+        import torch
+        for _ in range(warmup):
+            self.launch()
+        torch.cuda.synchronize()
+        out = []
+        for _ in range(batches):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                self.launch()
+            e1.record()
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) / steps)
+        return sorted(out)[len(out) // 2]
 
     def time_ms(self, steps, warmup):
         """Average launch duration from HIP events recorded on the launch stream."""
@@ -159,6 +204,7 @@ def main():
     sd = head.sched.describe()
     traffic = MEASURED_TRAFFIC_BYTES.get(((sd["tile_m"][0], sd["tile_n"][0], sd["tile_k"][0]),
                                           (sd["tile_m"][1], sd["tile_n"][1]), sd["direct_lds"]))
+    cold_ms, cold_sets = (None, 0) if args.only_headline else head.time_cold_ms()
     line = {
         "metric": "TFLOP/s and % of MFMA peak per operator on 1 MI355X; construction time (s)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -170,6 +216,8 @@ def main():
         "pct_of_mfma_peak": 100.0 * tflops / peak,
         "construct_s": head.construct_s,
         "wall_ms_per_step": wall_ms,
+        "cold_cache": None if cold_ms is None else {"ms_per_step": cold_ms, "tflops": w.flops / (cold_ms * 1e-3) / 1e12,
+                                                    "operand_sets": cold_sets},
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": peak, "unit": "TFLOP/s",
                      "frac": tflops / peak, "traffic": traffic},
     }
@@ -181,13 +229,20 @@ def main():
             if name == "cfg2":
                 continue
             c = Case(gs, inputs, wl)
-            m, _ = c.time_ms(steps2, max(3, args.warmup // 4))
+            m = c.time_median_ms(steps2, max(5, args.warmup // 4))
+            cold, _ = c.time_cold_ms()
             tf = wl.flops / (m * 1e-3) / 1e12
-            gb = _algorithmic_bytes(wl, inputs) / (m * 1e-3) / 1e9
-            ops_out.append({"workload": wl.name, "dtype": wl.dtype, "us": m * 1e3, "tflops": tf,
+            nbytes = _algorithmic_bytes(wl, inputs)
+            gb = nbytes / (m * 1e-3) / 1e9
+            ceiling = min(PEAK_TFLOPS[wl.dtype], wl.flops / nbytes * HBM_GBS / 1e3)     # TFLOP/s
+            ops_out.append({"workload": wl.name, "dtype": wl.dtype, "us": m * 1e3, "cold_us": cold * 1e3, "tflops": tf,
                             "pct_of_mfma_peak": 100.0 * tf / PEAK_TFLOPS[wl.dtype],
                             "algorithmic_GBs": gb, "pct_of_hbm_peak": 100.0 * gb / HBM_GBS,
+                            "roofline_ceiling_tflops": ceiling, "pct_of_roofline_ceiling": 100.0 * tf / ceiling,
                             "construct_s": c.construct_s, "kernel_id": c.sched.kernel_id,
+                            "schedule": "%dx%dx%d wave %dx%d stages %d direct %d" % (
+                                c.sched.tile[0][0], c.sched.tile[1][0], c.sched.tile[2][0], c.sched.tile[0][1],
+                                c.sched.tile[1][1], c.sched.stages, c.sched.direct_lds),
                             "parity_rel_frobenius_sampled": c.parity(256)})
             del c
             torch.cuda.empty_cache()

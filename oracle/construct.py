@@ -470,12 +470,14 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     gather = 4.0 if (view.bsrc == 2 and not direct) else 1.0
     scalar = 1.0 if vec else 6.0
     t_feed = scalar * e * kp * (bm + gather * bn) / l2_bw
-    overlap = 0.55 + 0.1 * min(resident * nwaves / hw.simds_per_cu, 3.0)
+    overlap = 0.7 + 0.1 * min(resident * nwaves / hw.simds_per_cu, 3.0)
     if direct:
         overlap += 0.05
-    t_main = max(t_mfma, t_lds, t_feed) / overlap
+    # every k tile boundary (barrier, refill of the fragment pipeline) exposes a share of the memory latency
+    t_ktile = 0.25 * hw.latency_ns[0] * 1e-3
+    t_main = max(t_mfma, t_lds, t_feed) / overlap + math.ceil(view.K / bk) * t_ktile
     hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units
-    t_epi = bm * bn * eo / (0.6 * hbm_bw_cu)
+    t_epi = bm * bn * eo / (0.8 * hbm_bw_cu)
     t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3
     t_cu = cu_tiles * (t_main + t_epi / resident) + t_fill
     bytes_total = view.batch * (e * (view.M * view.K + view.K * view.N) + eo * view.M * view.N)

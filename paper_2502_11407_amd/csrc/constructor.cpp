@@ -351,14 +351,16 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   const double t_feed = scalar * e * kp * (bm + gather * bn) / l2_bw;
   double par = resident * nwaves / hw.simds_per_cu;
   if (par > 3.0) par = 3.0;
-  double overlap = 0.55 + 0.1 * par;
+  double overlap = 0.7 + 0.1 * par;
   if (direct) overlap += 0.05;
   double t_main = t_mfma;
   if (t_lds > t_main) t_main = t_lds;
   if (t_feed > t_main) t_main = t_feed;
-  t_main = t_main / overlap;
+  // every k tile boundary (barrier, refill of the fragment pipeline) exposes a share of the memory latency
+  const double t_ktile = 0.25 * hw.latency_ns[0] * 1e-3;
+  t_main = t_main / overlap + std::ceil((double)v.K / bk) * t_ktile;
   const double hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units;
-  const double t_epi = bm * bn * eo / (0.6 * hbm_bw_cu);
+  const double t_epi = bm * bn * eo / (0.8 * hbm_bw_cu);
   const double t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3;
   const double t_cu = cu_tiles * (t_main + t_epi / resident) + t_fill;
   const double bytes_total = (double)v.batch * ((double)e * ((double)v.M * v.K + (double)v.K * v.N) + (double)eo * v.M * v.N);
