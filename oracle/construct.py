@@ -89,7 +89,7 @@ class View:
     batch: int = 1
     e: int = 2          # bytes per input element
     e_out: int = 4
-    bsrc: int = 0       # 0 k-contiguous B, 1 n-contiguous B, 2 convolution gather
+    bsrc: int = 0       # 0 k-contiguous B, 1 n-contiguous B, 2 convolution gather, 3 n-contiguous B sampled at stride 2
     conv: Optional[Tuple[int, ...]] = None   # convolution geometry (n, c, h, w, r, s, stride, pad), else None
     prepass: int = 0    # 1: a strided pointwise convolution (its input is compacted by a pre-pass kernel)
 

@@ -15,8 +15,10 @@ import lattice  # noqa: E402
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", HERE,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-mllvm", "-amdgpu-mfma-vgpr-form=1",      # accumulators stay in plain VGPRs: no copies to and from AGPRs around loops
          "-Wno-unused-command-line-argument"]
+# patch-staged convolution units only: accumulators stay in plain VGPRs (no copies to and from
+# AGPRs around the tap loop)
+CONV_FLAGS = ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]
 PER_TU = 4
 
 
@@ -31,17 +33,25 @@ def generate():
     os.makedirs(GEN, exist_ok=True)
     L = lattice.lattice()
     tus = []
-    for t in range(0, len(L), PER_TU):
-        group = L[t:t + PER_TU]
+    # translation units hold instances of one kernel template only (they are built with different flags)
+    ordered = [d for d in L if not d["units"]]
+    ordered += [None] * (-len(ordered) % PER_TU) + [d for d in L if d["units"]]
+    for t in range(0, len(ordered), PER_TU):
+        group = [d for d in ordered[t:t + PER_TU] if d is not None]
         src = ['#include "registry.hpp"', "namespace gensor {"]
         for d in group:
             src.append("typedef %s C_%d;" % (lattice.cfg_type(d), d["id"]))
             src.append("hipError_t launch_%d(const KernelArgs& a, hipStream_t st) { return %s<C_%d>(a, st); }"
                        % (d["id"], "launch_conv_instance" if d["units"] else "launch_instance", d["id"]))
         src.append("}  // namespace gensor\n")
-        path = os.path.join(GEN, "inst_%03d.hip" % (t // PER_TU))
+        path = os.path.join(GEN, "%s_%03d.hip" % ("conv" if group[0]["units"] else "inst", t // PER_TU))
         _write_if_changed(path, "\n".join(src))
         tus.append(path)
+    for f in os.listdir(GEN):                      # units of an earlier lattice
+        if f.endswith(".hip") and os.path.join(GEN, f) not in tus and f != "registry.hip":
+            os.remove(os.path.join(GEN, f))
+            if os.path.exists(os.path.join(GEN, f[:-4] + ".o")):
+                os.remove(os.path.join(GEN, f[:-4] + ".o"))
     reg = ['#include "registry.hpp"', "#if !defined(__HIP_DEVICE_COMPILE__)", "namespace gensor {"]
     for d in L:
         reg.append("hipError_t launch_%d(const KernelArgs&, hipStream_t);" % d["id"])
@@ -75,6 +85,8 @@ def _compile(src):
     # host sources: no fused multiply-add contraction, so the constructor's double arithmetic
     # is the plain IEEE sequence its tests compare against
     extra = ["-ffp-contract=off"] if src.endswith(".cpp") else []
+    if os.path.basename(src).startswith("conv_"):
+        extra += CONV_FLAGS
     cmd = [HIPCC] + FLAGS + extra + ["-x", "hip", "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)

@@ -366,7 +366,7 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   const double bytes_total = (double)v.batch * ((double)e * ((double)v.M * v.K + (double)v.K * v.N) + (double)eo * v.M * v.N);
   const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3);
   // soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)
-  const bool prepass = v.pointwise && v.cstride > 1;     // the input is compacted by a dependent launch of its own
+  const bool prepass = v.pointwise && v.cstride > 1 && v.bsrc != B_NCS2;   // the input is compacted by a dependent launch of its own
   return (t_cu > t_hbm ? t_cu : t_hbm) + 0.3 * (t_cu > t_hbm ? t_hbm : t_cu) + hw.launch_us * (prepass ? 3.5 : 1.0);
 }
 
@@ -385,11 +385,11 @@ bool usable(const InstanceDesc& d, const GemmView& v, bool vec_ok, bool ws_ok = 
 }  // namespace
 
 gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
-                                 uint64_t seed, bool vec_ok, bool ws_ok, bool allow_pointwise, gensor_schedule* out) {
+                                 uint64_t seed, bool vec_ok, bool ws_ok, int view_mode, gensor_schedule* out) {
   if (!p || !out) return GENSOR_ERR_INVALID_ARG;
   const auto t0 = std::chrono::steady_clock::now();
   GemmView v;
-  gensor_status st = gemm_view(p, &v, allow_pointwise);
+  gensor_status st = gemm_view(p, &v, view_mode);
   if (st != GENSOR_OK) return st;
   Ctx c;
   make_ctx(v, hw, opts, &c);
@@ -458,7 +458,7 @@ extern "C" const gensor_hw* gensor_hw_mi355x(void) { return &kMi355x; }
 
 extern "C" gensor_status gensor_construct(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
                                           uint64_t seed, gensor_schedule* out) {
-  return construct_internal(p, hw, opts, seed, true, true, true, out);
+  return construct_internal(p, hw, opts, seed, true, true, VIEW_DEFAULT, out);
 }
 
 extern "C" gensor_status gensor_construct_trace(const gensor_problem* p, const gensor_hw* hw,

@@ -96,30 +96,6 @@ __global__ __launch_bounds__(256) void subsample_input(const void* in, void* out
   }
 }
 
-// The same for stride 2 when W is a whole number of 16-byte vectors (so Q = W / 2 and every
-// output row is a whole number of half vectors): one 16-byte load, every other element kept,
-// one 8-byte store per thread.  groups = planes * P * Q / (EPC / 2) must fit 31 bits.
-template <int ES>
-__global__ __launch_bounds__(256) void subsample2_input(const void* in, void* out, int groups, int H, int W, int P, int Q) {
-  constexpr int EPC = 16 / ES, HALF = EPC / 2;
-  const int t = blockIdx.x * 256 + threadIdx.x;
-  if (t >= groups) return;
-  const int qg = Q / HALF;
-  const int row = t / qg, g = t - row * qg;          // row = plane * P + p
-  const int plane = row / P, p = row - plane * P;
-  const int64_t src = ((int64_t)plane * H + 2 * p) * W + g * EPC;
-  const u32x4 v = *(const u32x4*)((const char*)in + src * ES);
-  uint32_t o0, o1;
-  if constexpr (ES == 4) {
-    o0 = v[0]; o1 = v[2];
-  } else {
-    o0 = __builtin_amdgcn_perm(v[1], v[0], 0x05040100u);
-    o1 = __builtin_amdgcn_perm(v[3], v[2], 0x05040100u);
-  }
-  uint2 o = {o0, o1};
-  *(uint2*)((char*)out + (int64_t)t * 8) = o;
-}
-
 template <typename C>
 __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs args) {
   typedef typename C::T T;

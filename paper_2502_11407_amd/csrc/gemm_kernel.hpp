@@ -33,7 +33,9 @@
 
 namespace gensor {
 
-enum BSrc { B_KC = 0, B_NC = 1, B_CONV = 2 };
+// B_NCS2: n-contiguous B whose column n = p*Q + q is read at (2p)*W + 2q of a plane of H*W elements
+// (= ldb): the input of a pointwise convolution with stride 2, sampled while it is fetched.
+enum BSrc { B_KC = 0, B_NC = 1, B_CONV = 2, B_NCS2 = 3 };
 
 struct KernelArgs {
   const void* A;
@@ -176,6 +178,7 @@ struct Cfg {
   static_assert(MB == 32 || MB == 16, "MFMA block edge");
   static_assert(WAVES >= 1 && WAVES <= 16, "waves per workgroup");
   static_assert(!DIRECT || (VEC && BSRC == B_KC), "direct-to-LDS needs vector loads of k-contiguous operands");
+  static_assert(BSRC != B_NCS2 || VEC, "the sampled source exists only with vector loads");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS capacity");
 };
 
@@ -245,7 +248,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   const int rows_valid = min(BM, args.M - m0);
   const int cols_valid = min(BN, args.N - n0);
   const char* a_tile = Ab + (int64_t)m0 * args.lda * ES;
-  const char* b_tile = (C::BSRC == B_KC) ? Bb + (int64_t)n0 * args.ldb * ES : Bb + (int64_t)n0 * ES;
+  const char* b_tile = (C::BSRC == B_KC) ? Bb + (int64_t)n0 * args.ldb * ES : (C::BSRC == B_NCS2 ? Bb : Bb + (int64_t)n0 * ES);
   auto rsrc_a = [&](int k0) {
     return __builtin_amdgcn_make_buffer_rsrc((void*)(a_tile + (int64_t)k0 * ES), 0,
         clamp_records(((int64_t)(rows_valid - 1) * args.lda + (args.K - k0)) * ES), RSRC_FLAGS);
@@ -254,6 +257,9 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     if constexpr (C::BSRC == B_KC)
       return __builtin_amdgcn_make_buffer_rsrc((void*)(b_tile + (int64_t)k0 * ES), 0,
           clamp_records(((int64_t)(cols_valid - 1) * args.ldb + (args.K - k0)) * ES), RSRC_FLAGS);
+    else if constexpr (C::BSRC == B_NCS2)
+      return __builtin_amdgcn_make_buffer_rsrc((void*)(b_tile + (int64_t)k0 * args.ldb * ES), 0,
+          clamp_records((int64_t)(args.K - k0) * args.ldb * ES), RSRC_FLAGS);
     else
       return __builtin_amdgcn_make_buffer_rsrc((void*)(b_tile + (int64_t)k0 * args.ldb * ES), 0,
           clamp_records(((int64_t)(args.K - k0 - 1) * args.ldb + (args.N - n0)) * ES), RSRC_FLAGS);
@@ -274,6 +280,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     a_kch[i] = ch * EPC;
   }
   uint32_t b_voff[C::B_LOADS], b_kch[C::B_LOADS];
+  uint32_t b_voff2[C::BSRC == B_NCS2 ? C::B_LOADS : 1];      // second half of a sampled chunk
 #pragma unroll
   for (int i = 0; i < C::B_LOADS; ++i) {
     const int q = tid + i * C::THREADS;
@@ -281,6 +288,17 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::CPR);
       b_voff[i] = (uint32_t)((row * (int)args.ldb + ch * EPC) * ES);
       b_kch[i] = ch * EPC;
+    } else if constexpr (C::BSRC == B_NCS2) {
+      // chunk = EPC consecutive columns = two halves of EPC/2 columns, each inside one output
+      // row (Q is a multiple of EPC/2) and so one 16-byte run of the input row it samples
+      constexpr int CPRN = BN * ES / 16;
+      const int krow = q / CPRN, ch = q % CPRN;
+      const int nA = n0 + ch * EPC, nB = nA + EPC / 2;
+      const int pA = nA / args.cQ, pB = nB / args.cQ;
+      const int sA = (2 * pA) * args.cW + 2 * (nA - pA * args.cQ), sB = (2 * pB) * args.cW + 2 * (nB - pB * args.cQ);
+      b_voff[i] = nA < args.N ? (uint32_t)((krow * (int)args.ldb + sA) * ES) : OOB;
+      b_voff2[i] = nB < args.N ? (uint32_t)((krow * (int)args.ldb + sB) * ES) : OOB;
+      b_kch[i] = krow;
     } else {
       constexpr int CPRN = BN * ES / 16;
       const int krow = q / CPRN, ch = q % CPRN;
@@ -291,7 +309,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 
   // ---- staging registers (global -> registers -> LDS)
   u32x4 ra[C::DIRECT ? 1 : C::A_LOADS];
-  u32x4 rb[C::DIRECT ? 1 : C::B_LOADS];
+  u32x4 rb[C::DIRECT ? 1 : C::B_LOADS * (C::BSRC == B_NCS2 ? 2 : 1)];
 
   // element-wise access for the scalar path and the convolution gather
   auto a_elem_bits = [&](int row, int k) -> uint32_t {
@@ -381,11 +399,15 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         if (C::B_CHUNKS % C::THREADS != 0 && tid + i * C::THREADS >= C::B_CHUNKS) break;
         uint32_t off = b_voff[i];
         if constexpr (C::BSRC == B_KC) off = (full || (int)b_kch[i] < args.K - k0) ? off : OOB;
-        if constexpr (C::DIRECT)
+        if constexpr (C::DIRECT) {
           __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (GENSOR_LDS void*)(lds + st * C::STAGE_BYTES + C::A_BYTES + (i * C::THREADS + wave * 64) * 16),
                                                    16, off, 0, 0, 0);
-        else
+        } else if constexpr (C::BSRC == B_NCS2) {
+          rb[2 * i] = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+          rb[2 * i + 1] = __builtin_amdgcn_raw_buffer_load_b128(r, b_voff2[i], 0, 0);
+        } else {
           rb[i] = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+        }
       }
     }
   };
@@ -406,6 +428,20 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         if (C::B_CHUNKS % C::THREADS != 0 && q >= C::B_CHUNKS) break;
         if constexpr (C::BSRC == B_KC) {
           *(GENSOR_LDS u32x4*)(bbase + q * 16) = rb[i];
+        } else if constexpr (C::BSRC == B_NCS2) {
+          // keep every other element of the two 16-byte runs
+          constexpr int CPRN = BN * ES / 16;
+          const u32x4 v0 = rb[2 * i], v1 = rb[2 * i + 1];
+          u32x4 o;
+          if constexpr (ES == 4) {
+            o[0] = v0[0]; o[1] = v0[2]; o[2] = v1[0]; o[3] = v1[2];
+          } else {
+            o[0] = __builtin_amdgcn_perm(v0[1], v0[0], 0x05040100u);
+            o[1] = __builtin_amdgcn_perm(v0[3], v0[2], 0x05040100u);
+            o[2] = __builtin_amdgcn_perm(v1[1], v1[0], 0x05040100u);
+            o[3] = __builtin_amdgcn_perm(v1[3], v1[2], 0x05040100u);
+          }
+          *(GENSOR_LDS u32x4*)(bbase + (q / CPRN) * C::PITCH_N + (q % CPRN) * 16) = o;
         } else {
           constexpr int CPRN = BN * ES / 16;
           *(GENSOR_LDS u32x4*)(bbase + (q / CPRN) * C::PITCH_N + (q % CPRN) * 16) = rb[i];

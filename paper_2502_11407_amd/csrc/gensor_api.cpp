@@ -31,7 +31,7 @@ namespace gensor {
 
 static bool valid_dtype(int d) { return d == GENSOR_F32 || d == GENSOR_F16 || d == GENSOR_BF16; }
 
-gensor_status gemm_view(const gensor_problem* p, GemmView* v, bool allow_pointwise) {
+gensor_status gemm_view(const gensor_problem* p, GemmView* v, int mode) {
   if (!p || !v) return GENSOR_ERR_INVALID_ARG;
   if (!valid_dtype(p->in_dtype) || !valid_dtype(p->out_dtype)) return GENSOR_ERR_INVALID_ARG;
   if (p->out_dtype != GENSOR_F32 && p->out_dtype != p->in_dtype) return GENSOR_ERR_UNSUPPORTED;
@@ -61,12 +61,13 @@ gensor_status gemm_view(const gensor_problem* p, GemmView* v, bool allow_pointwi
     v->bsrc = B_CONV;
     v->cn = p->n; v->cc = p->c; v->ch = p->h; v->cw = p->w; v->cr = p->r; v->cs = p->s;
     v->cstride = p->stride; v->cpad = p->pad;
-    if (allow_pointwise && p->r == 1 && p->s == 1 && p->pad == 0) {
+    if (mode != VIEW_GENERAL && p->r == 1 && p->s == 1 && p->pad == 0) {
       v->pointwise = 1;
       v->N = v->P * v->Q;
       v->K = p->c;
       v->batch = p->n;
-      v->bsrc = B_NC;
+      // stride 2 on rows that are whole 16-byte vectors: sampled while fetched, no pre-pass
+      v->bsrc = (mode == VIEW_DEFAULT && p->stride == 2 && p->w % (16 / v->esize) == 0) ? B_NCS2 : B_NC;
     }
   } else {
     return GENSOR_ERR_INVALID_ARG;
@@ -158,7 +159,7 @@ bool vector_ok(const GemmView& v, const void* A, int64_t lda, int64_t strideA, c
   auto al = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
   if (!al(A) || lda % epc || strideA % epc || v.K % epc) return false;
   if (v.bsrc == B_KC) return al(B) && ldb % epc == 0 && strideB % epc == 0;
-  if (v.bsrc == B_NC) return al(B) && ldb % epc == 0 && strideB % epc == 0 && v.N % epc == 0;
+  if (v.bsrc == B_NC || v.bsrc == B_NCS2) return al(B) && ldb % epc == 0 && strideB % epc == 0 && v.N % epc == 0;
   return al(B);  // convolution: the gather is element-wise; the patch path reads 16-byte vectors
 }
 
@@ -177,7 +178,7 @@ extern "C" gensor_status gensor_instance_schedule(int32_t id, const gensor_probl
 namespace gensor {
 // Bytes of the compacted input of a strided pointwise convolution (0: the input is used as it is).
 static size_t pointwise_workspace(const GemmView& v) {
-  return v.pointwise && v.cstride > 1 ? (size_t)(v.batch * v.K * v.N * v.esize) : 0;
+  return v.pointwise && v.cstride > 1 && v.bsrc != B_NCS2 ? (size_t)(v.batch * v.K * v.N * v.esize) : 0;
 }
 }  // namespace gensor
 
@@ -185,12 +186,14 @@ static size_t pointwise_workspace(const GemmView& v) {
 // writes into the caller's workspace; a strided pointwise convolution run as a batched GEMM
 // reads a compacted copy of the input from it; nothing else needs one.
 extern "C" size_t gensor_workspace_bytes(const gensor_schedule* s, const gensor_problem* p) {
-  GemmView v, g;
-  if (!p || p->op != GENSOR_OP_CONV2D || gemm_view(p, &v) != GENSOR_OK || gemm_view(p, &g, false) != GENSOR_OK) return 0;
+  GemmView v, w, g;
+  if (!p || p->op != GENSOR_OP_CONV2D || gemm_view(p, &v) != GENSOR_OK || gemm_view(p, &w, VIEW_PREPASS) != GENSOR_OK ||
+      gemm_view(p, &g, VIEW_GENERAL) != GENSOR_OK) return 0;
   const size_t need_patch = (size_t)(g.M * g.K * g.esize);
-  const size_t need_pw = pointwise_workspace(v);
+  const size_t need_pw = pointwise_workspace(w);
   if (!s) return need_patch > need_pw ? need_patch : need_pw;   // what any schedule the library may construct can ask for
-  if (v.pointwise && find_instance(s, v)) return need_pw;
+  if (v.pointwise && find_instance(s, v)) return pointwise_workspace(v);
+  if (w.pointwise && find_instance(s, w)) return need_pw;
   const InstanceDesc* d = find_instance(s, g);
   return d && d->units ? need_patch : 0;
 }
@@ -202,9 +205,9 @@ namespace {
 std::mutex g_memo_mutex;
 std::map<std::tuple<int, int, int, int, int, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int>, gensor_schedule> g_memo;
 
-gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, bool ws_ok, bool pointwise, gensor_schedule* out) {
+gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, bool ws_ok, int view_mode, gensor_schedule* out) {
   auto key = std::make_tuple((int)p->op, (int)p->in_dtype, (int)p->out_dtype, (int)p->transB,
-                             (vec_ok ? 1 : 0) + (ws_ok ? 2 : 0) + (pointwise ? 4 : 0),
+                             (vec_ok ? 1 : 0) + (ws_ok ? 2 : 0) + 4 * view_mode,
                              p->op == GENSOR_OP_CONV2D ? p->n : p->batch, p->op == GENSOR_OP_CONV2D ? p->c : p->M,
                              p->op == GENSOR_OP_CONV2D ? p->h : p->N, p->op == GENSOR_OP_CONV2D ? p->w : p->K,
                              p->op == GENSOR_OP_CONV2D ? p->k : 0, p->op == GENSOR_OP_CONV2D ? p->r : 0,
@@ -213,7 +216,7 @@ gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, bool ws_ok
   std::lock_guard<std::mutex> lock(g_memo_mutex);
   auto it = g_memo.find(key);
   if (it != g_memo.end()) { *out = it->second; return GENSOR_OK; }
-  gensor_status st = construct_internal(p, nullptr, nullptr, 0, vec_ok, ws_ok, pointwise, out);
+  gensor_status st = construct_internal(p, nullptr, nullptr, 0, vec_ok, ws_ok, view_mode, out);
   if (st == GENSOR_OK) g_memo[key] = *out;
   return st;
 }
@@ -226,7 +229,8 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
                      workspace_bytes >= (size_t)(v.M * v.K * v.esize);
   gensor_schedule local;
   if (!s) {
-    gensor_status st = memoised_schedule(p, vec_ok, ws_ok, v.pointwise != 0, &local);
+    const int mode = !v.pointwise ? VIEW_GENERAL : (v.cstride > 1 && v.bsrc == B_NC ? VIEW_PREPASS : VIEW_DEFAULT);
+    gensor_status st = memoised_schedule(p, vec_ok, ws_ok, mode, &local);
     if (st != GENSOR_OK) return st;
     s = &local;
   }
@@ -239,7 +243,7 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
   const int64_t lim = 0x7fffffffll;
   if ((int64_t)(d->bm + 1) * lda * v.esize >= lim || (int64_t)(d->bm + 1) * ldc * v.osize >= lim) return GENSOR_ERR_UNSUPPORTED;
   if (v.bsrc == B_KC && (int64_t)(d->bn + 1) * ldb * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
-  if (v.bsrc == B_NC && ((int64_t)(d->bk + 1) * ldb + d->bn) * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
+  if ((v.bsrc == B_NC || v.bsrc == B_NCS2) && ((int64_t)(d->bk + 1) * ldb + d->bn) * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
 
   KernelArgs a;
   std::memset(&a, 0, sizeof(a));
@@ -263,7 +267,7 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
     a.cInBytes = pl.in_bytes; a.cWBytes = pl.w_bytes; a.cOutBytes = pl.out_bytes;
     a.batch = 1;
   }
-  if (v.bsrc == B_CONV) {
+  if (v.bsrc == B_CONV || v.bsrc == B_NCS2) {
     a.cC = (int32_t)p->c; a.cH = (int32_t)p->h; a.cW = (int32_t)p->w; a.cR = (int32_t)p->r; a.cS = (int32_t)p->s;
     a.cP = (int32_t)v.P; a.cQ = (int32_t)v.Q; a.cStride = (int32_t)p->stride; a.cPad = (int32_t)p->pad;
   }
@@ -307,50 +311,45 @@ extern "C" gensor_status gensor_conv2d(const gensor_schedule* s, const gensor_pr
   if (st != GENSOR_OK) return st;
   if (v.pointwise) {
     // one GEMM per image: A = filters [k][c] shared by all images, B = the (sampled) input
-    // [c][P*Q] of the image, C = its output [k][P*Q].  An explicit schedule may instead name
-    // an instance of the general view; without the workspace a strided input needs, a NULL
-    // schedule falls back to the general view as well.
-    const size_t need = pointwise_workspace(v);
-    const bool have = need == 0 || (workspace && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0 && workspace_bytes >= need);
-    bool use = have;
-    if (s) {
-      if (find_instance(s, v)) { if (!have) return GENSOR_ERR_WORKSPACE; }
-      else use = false;
-    }
-    if (use) {
+    // [c][P*Q] of the image, C = its output [k][P*Q].  Views are tried in order of
+    // preference: sampled while fetched (stride 2, no workspace), compacted by a pre-pass
+    // (needs the workspace), then the general implicit GEMM.  An explicit schedule selects
+    // the view whose instance it names.
+    const int64_t PQ = v.N;
+    for (int mode = VIEW_DEFAULT; mode <= VIEW_PREPASS; ++mode) {
+      GemmView w;
+      st = gemm_view(p, &w, mode);
+      if (st != GENSOR_OK) return st;
+      if (mode == VIEW_PREPASS && w.bsrc == v.bsrc) break;          // the same view again
+      const size_t need = pointwise_workspace(w);
+      const bool have = need == 0 || (workspace && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0 && workspace_bytes >= need);
+      const int64_t ldb = need ? PQ : p->h * p->w;
+      if (s) {
+        if (!find_instance(s, w)) continue;
+        if (!have) return GENSOR_ERR_WORKSPACE;
+      } else {
+        if (!have) continue;
+        if (w.bsrc == B_NCS2 && !vector_ok(w, weight, w.K, 0, input, ldb, w.K * ldb)) continue;   // sampled instances are vector-only
+      }
       const void* X = input;
-      const int64_t PQ = v.N;
       if (need) {
         const int64_t planes = p->n * p->c;
-        const int epc = 16 / v.esize;
-        hipStream_t stream = (hipStream_t)hip_stream;
-        const int64_t groups = planes * PQ / (epc / 2);
-        if (p->stride == 2 && p->w % epc == 0 && (reinterpret_cast<uintptr_t>(input) & 15u) == 0 && groups < INT32_MAX) {
-          const unsigned blocks = (unsigned)((groups + 255) / 256);
-          if (v.esize == 4)
-            hipLaunchKernelGGL(subsample2_input<4>, dim3(blocks), dim3(256), 0, stream, input, workspace, (int)groups,
-                               (int)p->h, (int)p->w, (int)v.P, (int)v.Q);
-          else
-            hipLaunchKernelGGL(subsample2_input<2>, dim3(blocks), dim3(256), 0, stream, input, workspace, (int)groups,
-                               (int)p->h, (int)p->w, (int)v.P, (int)v.Q);
-        } else {
-          const int64_t threads = (planes * PQ + epc - 1) / epc;
-          if ((threads + 255) / 256 > INT32_MAX) return GENSOR_ERR_UNSUPPORTED;
-          const unsigned blocks = (unsigned)((threads + 255) / 256);
-          if (v.esize == 4)
-            hipLaunchKernelGGL(subsample_input<4>, dim3(blocks), dim3(256), 0, stream, input, workspace, planes,
-                               (int)p->h, (int)p->w, (int)v.P, (int)v.Q, (int)p->stride);
-          else
-            hipLaunchKernelGGL(subsample_input<2>, dim3(blocks), dim3(256), 0, stream, input, workspace, planes,
-                               (int)p->h, (int)p->w, (int)v.P, (int)v.Q, (int)p->stride);
-        }
+        const int epc = 16 / w.esize;
+        const int64_t threads = (planes * PQ + epc - 1) / epc;
+        if ((threads + 255) / 256 > INT32_MAX) return GENSOR_ERR_UNSUPPORTED;
+        const unsigned blocks = (unsigned)((threads + 255) / 256);
+        if (w.esize == 4)
+          hipLaunchKernelGGL(subsample_input<4>, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, input, workspace, planes,
+                             (int)p->h, (int)p->w, (int)w.P, (int)w.Q, (int)p->stride);
+        else
+          hipLaunchKernelGGL(subsample_input<2>, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, input, workspace, planes,
+                             (int)p->h, (int)p->w, (int)w.P, (int)w.Q, (int)p->stride);
         if (hipGetLastError() != hipSuccess) return GENSOR_ERR_DEVICE;
         X = workspace;
       }
-      const int64_t ldb = need ? PQ : p->h * p->w;
-      return run(s, p, v, 1.0f, weight, v.K, 0, X, ldb, v.K * ldb, 0.0f, output, PQ, v.M * PQ, nullptr, 0, hip_stream);
+      return run(s, p, w, 1.0f, weight, w.K, 0, X, ldb, w.K * ldb, 0.0f, output, PQ, w.M * PQ, nullptr, 0, hip_stream);
     }
-    st = gemm_view(p, &v, false);
+    st = gemm_view(p, &v, VIEW_GENERAL);
     if (st != GENSOR_OK) return st;
   }
   // A = filters [k][c*r*s] (k-contiguous), B = gathered input, C = output viewed per image.

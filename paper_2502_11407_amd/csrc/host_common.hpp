@@ -28,16 +28,20 @@ bool conv_patch_plan(const InstanceDesc& d, const GemmView& v, ConvPlan* plan);
 
 // A pointwise convolution (1x1 filter, no padding) is O[img] = W[k][c] * X[img][c][P*Q] with
 // X the input sampled at the stride: a batched GEMM over the images with an n-contiguous B.
-// allow_pointwise = false gives the general implicit-GEMM view of the same problem instead.
-gensor_status gemm_view(const gensor_problem* p, GemmView* v, bool allow_pointwise = true);
+// VIEW_DEFAULT takes that view; with stride 2 and rows of whole 16-byte vectors the kernel
+// samples the input while fetching it (B_NCS2), any other stride > 1 needs the input compacted
+// into the workspace first (B_NC).  VIEW_PREPASS always compacts; VIEW_GENERAL gives the
+// general implicit-GEMM view.  The three agree for every other operator.
+enum ViewMode { VIEW_GENERAL = 0, VIEW_DEFAULT = 1, VIEW_PREPASS = 2 };
+gensor_status gemm_view(const gensor_problem* p, GemmView* v, int mode = VIEW_DEFAULT);
 void schedule_from_instance(const InstanceDesc& d, gensor_schedule* s);
 bool instance_serves(const InstanceDesc& d, const GemmView& v);
 const InstanceDesc* find_instance(const gensor_schedule* s, const GemmView& v);
 
 // gensor_construct with three more inputs: whether the operands allow 16-byte vector accesses,
-// whether the caller supplied the workspace that patch-staged convolutions need, and whether a
-// pointwise convolution may take its batched-GEMM view.
+// whether the caller supplied the workspace that patch-staged convolutions need, and the
+// view (ViewMode) a pointwise convolution is taken in.
 gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
-                                 uint64_t seed, bool vec_ok, bool ws_ok, bool allow_pointwise, gensor_schedule* out);
+                                 uint64_t seed, bool vec_ok, bool ws_ok, int view_mode, gensor_schedule* out);
 
 }  // namespace gensor

@@ -4,7 +4,7 @@ build.py turns this list into one translation unit per instance plus the registr
 from itertools import product
 
 DT = {"f32": 0, "f16": 1, "bf16": 2}
-BSRC = {"KC": 0, "NC": 1, "CONV": 2}
+BSRC = {"KC": 0, "NC": 1, "CONV": 2, "NCS2": 3}
 CT = {"f32": "f32_t", "f16": "f16_t", "bf16": "bf16_t"}
 
 
@@ -51,6 +51,10 @@ def lattice():
                 out.append(_inst(dt, "f32", bm, bn, bk, wm, wn, mb, vm, vn, bsrc))
             # scalar-access instance: any alignment, any extents
             out.append(_inst(dt, "f32", 64, 64, 32, 32, 32, 16, 1, 1, bsrc, vec=0))
+        # pointwise convolution with stride 2: the n-contiguous B operand sampled while it is fetched
+        for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles16:
+            if bm * bn >= 64 * 64 and (vm, vn) == (1, 1) and bk == 64 and mb == 32 and wm * wn < 128 * 128:
+                out.append(_inst(dt, "f32", bm, bn, bk, wm, wn, mb, vm, vn, "NCS2"))
         # direct global->LDS staging for k-contiguous operands
         for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles16:
             if bm * bn >= 128 * 128:
@@ -81,6 +85,8 @@ def lattice():
         (32, 32, 32, 16, 16, 16, 1, 1),
         (64, 32, 32, 32, 16, 16, 1, 1),
     ]
+    for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles32[:3:2]:
+        out.append(_inst("f32", "f32", bm, bn, bk, wm, wn, mb, vm, vn, "NCS2"))
     for bsrc in ("KC", "NC", "CONV"):
         for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles32:
             out.append(_inst("f32", "f32", bm, bn, bk, wm, wn, mb, vm, vn, bsrc))

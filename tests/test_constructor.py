@@ -262,7 +262,9 @@ def _views():
          oc.View(64, 32 * 56 * 56, 576, 1, 2, 4, 2, conv=(32, 64, 56, 56, 3, 3, 1, 1))),
         # pointwise convolution (1x1, no padding): one GEMM per image with an n-contiguous B
         (gs.conv_problem("f16", 32, 256, 56, 56, 512, 1, 1, 2, 0),
-         oc.View(512, 28 * 28, 256, 32, 2, 4, 1, conv=(32, 256, 56, 56, 1, 1, 2, 0), prepass=1)),
+         oc.View(512, 28 * 28, 256, 32, 2, 4, 3, conv=(32, 256, 56, 56, 1, 1, 2, 0))),
+        (gs.conv_problem("f16", 8, 64, 27, 27, 128, 1, 1, 2, 0),
+         oc.View(128, 14 * 14, 64, 8, 2, 4, 1, conv=(8, 64, 27, 27, 1, 1, 2, 0), prepass=1)),
         (gs.conv_problem("f16", 32, 256, 56, 56, 512, 1, 1, 2, 1),
          oc.View(512, 32 * 29 * 29, 256, 1, 2, 4, 2, conv=(32, 256, 56, 56, 1, 1, 2, 1))),
         (gs.conv_problem("f32", 4, 24, 13, 11, 40, 3, 2, 2, 1),

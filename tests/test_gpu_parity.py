@@ -51,11 +51,15 @@ def instance_cases(gs):
     for idx in range(gs.num_instances()):
         for dt in ("f32", "f16", "bf16"):
             for out_dt in sorted({"f32", dt}):
-                for tb, op in ((1, "gemm"), (0, "gemm"), (0, "conv"), (0, "conv1x1")):
+                for tb, op in ((1, "gemm"), (0, "gemm"), (0, "conv"), (0, "conv1x1"), (0, "conv_pw2")):
                     if op == "conv1x1" and out and out[-1][0] == idx:
                         continue                      # already covered with 3x3 filters
-                    p = (gs.conv_problem(dt, 1, 8, 8, 8, 8, 3 if op == "conv" else 1, 3 if op == "conv" else 1, 1, 1, out_dt)
-                         if op.startswith("conv") else gs.gemm_problem(dt, 64, 64, 64, 0, tb, 1, out_dt))
+                    if op == "conv_pw2":              # pointwise, stride 2: the sampling B source
+                        p = gs.conv_problem(dt, 1, 8, 8, 16, 8, 1, 1, 2, 0, out_dt)
+                    elif op.startswith("conv"):
+                        p = gs.conv_problem(dt, 1, 8, 8, 8, 8, 3 if op == "conv" else 1, 3 if op == "conv" else 1, 1, 1, out_dt)
+                    else:
+                        p = gs.gemm_problem(dt, 64, 64, 64, 0, tb, 1, out_dt)
                     s = gs.instance_schedule(idx, p)
                     if s is not None:
                         out.append((idx, dt, out_dt, op, tb, s))
@@ -87,10 +91,14 @@ def test_every_instance_bit_exact_on_integers(gs):
                 c, r = 24, 1
             k = bm + 5
             n, h, w = 2, 9, max(7, bn // 8)
+            stride, pad = 1, 1
+            if op == "conv_pw2":                    # P = 9, Q = bn/8: P*Q spans a tile and a ragged tail
+                c, r, stride, pad = 24, 1, 2, 0
+                h, w = 17, 2 * max(8, bn // 8)
             I = inputs.small_ints(300 + idx, (n, c, h, w), dt, -min(lim, 2), min(lim, 2))
             W = inputs.small_ints(400 + idx, (k, c, r, r), dt, -min(lim, 2), min(lim, 2))
-            want = ops.conv2d(I, W, dt, stride=1, pad=1)
-            p = gs.conv_problem(dt, n, c, h, w, k, r, r, 1, 1, out_dt)
+            want = ops.conv2d(I, W, dt, stride=stride, pad=pad)
+            p = gs.conv_problem(dt, n, c, h, w, k, r, r, stride, pad, out_dt)
             dO = gs.empty_device(want.shape, out_dt)
             dO.fill_(float("nan"))
             gs.conv2d(p, gs.to_device(I, dt), gs.to_device(W, dt), dO, s, gs.conv_workspace(p, s))
@@ -213,9 +221,11 @@ def test_conv_patch_instances_bit_exact(gs, dtype, geom):
 @pytest.mark.parametrize("geom", [
     # n, c, h, w, k, stride
     (3, 40, 12, 16, 70, 1),      # the input itself is the B operand (ldb = H*W)
-    (3, 40, 12, 16, 70, 2),      # compacted through the workspace; P*Q = 48
-    (2, 24, 13, 11, 33, 3),      # P*Q = 20: not a whole number of 16-byte chunks, scalar instances only
-    (2, 16, 31, 31, 16, 2),      # P*Q = 256, several n tiles
+    (3, 40, 12, 16, 70, 2),      # stride 2, rows of whole vectors: sampled while fetched, no workspace; P*Q = 48
+    (2, 16, 16, 40, 300, 2),     # the same over several m and n tiles with ragged edges; P*Q = 160
+    (2, 24, 13, 11, 33, 3),      # compacted through the workspace; P*Q = 20: scalar instances only
+    (2, 16, 31, 31, 16, 2),      # compacted through the workspace; P*Q = 256, several n tiles
+    (2, 8, 9, 24, 20, 2),        # could be sampled, but P*Q = 60 is no whole number of fp16 vectors: compacted
 ])
 def test_pointwise_conv_is_a_batched_gemm(gs, dtype, geom):
     """1x1 filter, no padding: every n-contiguous-B GEMM instance that serves the per-image view,
@@ -229,13 +239,15 @@ def test_pointwise_conv_is_a_batched_gemm(gs, dtype, geom):
     dI, dW = gs.to_device(I, dtype), gs.to_device(W, dtype)
     pq = want.shape[2] * want.shape[3]
     esize = 4 if dtype == "f32" else 2
-    assert gs.workspace_bytes(p) >= (n * c * pq * esize if stride > 1 else 0)
+    sampled = stride == 2 and w % (16 // esize) == 0          # instance_schedule then offers the sampling instances
+    need = 0 if (stride == 1 or sampled) else n * c * pq * esize
+    assert gs.workspace_bytes(p) >= need
     ran = 0
     for idx in range(gs.num_instances()):
         sch = gs.instance_schedule(idx, p)
         if sch is None or (sch.vec_bytes == 16 and pq % (16 // esize)):
             continue
-        assert gs.workspace_bytes(p, sch) == (n * c * pq * esize if stride > 1 else 0)
+        assert gs.workspace_bytes(p, sch) == need
         print(f"pointwise conv instance {idx} tile {sch.tile[0][0]}x{sch.tile[1][0]}x{sch.tile[2][0]} geom {geom} {dtype}", flush=True)
         dO = gs.empty_device(want.shape)
         dO.fill_(float("nan"))
@@ -243,12 +255,12 @@ def test_pointwise_conv_is_a_batched_gemm(gs, dtype, geom):
         torch.cuda.synchronize()
         got = gs.to_host_f64(dO)
         assert np.array_equal(got, want), f"instance {idx}: max abs diff {np.nanmax(np.abs(got - want))}"
-        if stride > 1:
+        if need:
             with pytest.raises(gs.GensorError) as e:
                 gs.conv2d(p, dI, dW, dO, sch)               # the schedule needs the compacted input
             assert e.value.status == 4
         ran += 1
-    assert ran >= (1 if pq % (16 // esize) else 2)
+    assert ran >= (2 if pq % (16 // esize) == 0 else (0 if sampled else 1))
     for ws in (gs.conv_workspace(p), None):                  # None: strided input falls back to the general view
         dO = gs.empty_device(want.shape)
         dO.fill_(float("nan"))
