@@ -151,6 +151,25 @@ class Case:
         return ops.rel_frobenius(got.double().cpu().numpy(), want)
 
 
+def mfma_ceiling(gs, inputs, dtype, iters=20000):
+    """TFLOP/s of a kernel of nothing but dense MFMAs whose operands are drawn like the headline's
+    inputs (uniform [-1, 1)): the rate the chip's power limit allows for such values."""
+    import torch
+    vals = inputs.uniform_pm1(99, (128 * 1024,), dtype)                         # 256 KiB of operand fragments
+    ops_dev = gs.to_device(vals, dtype)
+    sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        gs.mfma_probe(dtype, ops_dev, sink, iters)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    gs.mfma_probe(dtype, ops_dev, sink, iters)
+    e1.record()
+    torch.cuda.synchronize()
+    flops = gs.hw_mi355x().compute_units * 4.0 * iters * 8 * 2 * 32 * 32 * 16
+    return flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
 def cpu_baseline(w):
     """The oracle as it stands on a bounded slice (leading rows of A) of the headline GEMM."""
     from oracle import ops
@@ -172,8 +191,9 @@ def cpu_baseline(w):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=300,
+                    help="untimed launches first; the shader clock needs tens of milliseconds of load to settle")
     ap.add_argument("--only-headline", action="store_true", help="skip the other operator shapes and the CPU legs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy, the known-size reference for HBM byte counters")
@@ -222,9 +242,14 @@ def main():
                      "frac": tflops / peak, "traffic": traffic},
     }
     if not args.only_headline:
+        ceil_tf = mfma_ceiling(gs, inputs, w.dtype)
+        line["mfma_only_kernel_same_operand_distribution"] = {
+            "tflops": ceil_tf, "frac_of_it": tflops / ceil_tf,
+            "note": "a kernel of nothing but fp16 MFMAs on uniform[-1,1) operands, timed in this run: the chip's power "
+                    "limit holds it below the published peak, so this is the ceiling that applies to this workload"}
         line["parity_rel_frobenius_sampled"] = head.parity()
         ops_out = []
-        steps2 = max(10, args.steps // 4)
+        steps2 = min(200, max(10, args.steps // 4))
         for name, wl in inputs.all_configs().items():
             if name == "cfg2":
                 continue

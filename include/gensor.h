@@ -195,6 +195,20 @@ gensor_status gensor_conv2d(const gensor_schedule* s, const gensor_problem* p,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 size_t gensor_workspace_bytes(const gensor_schedule* s, const gensor_problem* p);
+
+/*
+ * Measurement aid, not an operator: launches a kernel of nothing but dense 16-bit MFMAs
+ * (one workgroup of 4 wavefronts per CU, 8 independent 32x32 accumulators per wavefront,
+ * `iters` rounds of 8 instructions) whose A and B fragments are loaded once from
+ * `operands` (device memory, 256 KiB, 16-byte aligned; the caller chooses the values).
+ * The MFMA rate a chip sustains depends on the operand values through its power limit;
+ * timing this launch with the operator's own input distribution gives the ceiling that
+ * applies to it.  `sink` (device, 256 * 256 floats) receives one value per lane so the
+ * work cannot be dropped.  in_dtype is GENSOR_F16 or GENSOR_BF16.  Flop count of one
+ * launch: compute_units * 4 * iters * 8 * 2 * 32 * 32 * 16.
+ */
+gensor_status gensor_mfma_probe(gensor_dtype in_dtype, const void* operands, float* sink,
+                                int32_t iters, void* hip_stream);
 const char* gensor_status_string(gensor_status st);
 
 #ifdef __cplusplus

@@ -23,7 +23,7 @@ OP_GEMM, OP_BMM, OP_CONV2D = 0, 1, 2
 
 EXPORTS = ["gensor_hw_mi355x", "gensor_construct", "gensor_construct_trace", "gensor_predict_us",
            "gensor_num_instances", "gensor_instance_schedule", "gensor_gemm", "gensor_bmm", "gensor_conv2d",
-           "gensor_workspace_bytes", "gensor_status_string"]
+           "gensor_workspace_bytes", "gensor_status_string", "gensor_mfma_probe"]
 
 
 class Problem(C.Structure):
@@ -101,6 +101,8 @@ def _load():
     L.gensor_conv2d.argtypes = [S, P, vp, vp, vp, vp, C.c_size_t, vp]
     L.gensor_workspace_bytes.restype = C.c_size_t
     L.gensor_workspace_bytes.argtypes = [S, P]
+    L.gensor_mfma_probe.restype = i32
+    L.gensor_mfma_probe.argtypes = [i32, vp, vp, i32, vp]
     return L
 
 
@@ -228,6 +230,13 @@ def to_device(arr: np.ndarray, dtype: str):
     if dtype == "bf16":
         return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).cuda().view(torch.bfloat16)
     return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+
+def mfma_probe(dtype: str, operands, sink, iters: int, stream=None):
+    """Launch the MFMA-only probe kernel (measurement aid): `operands` is a 256 KiB device tensor whose
+    values are the A and B fragments, `sink` a device tensor of 65536 floats."""
+    st = lib.gensor_mfma_probe(DTYPE[dtype], operands.data_ptr(), sink.data_ptr(), iters, _stream_ptr(stream))
+    _check(st, "gensor_mfma_probe")
 
 
 def conv_workspace(p: Problem, schedule: Optional[Schedule] = None):

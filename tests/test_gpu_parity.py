@@ -368,3 +368,17 @@ def test_benchmark_shapes_full_size_sampled(gs, name):
     assert err <= 2e-6
     scale = np.abs(want).max()
     assert np.abs(got - want).max() <= 1e-4 * scale
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_mfma_probe_counts_its_flops(gs, dtype):
+    """The measurement aid really executes iters x 8 MFMAs per wavefront: with all-ones operands every
+    accumulator element ends at 16 * iters, so a lane's sum over its 8 x 16 values is 2048 * iters."""
+    import torch
+    ones = inputs.to_storage(np.ones(128 * 1024, dtype=np.float32), dtype)
+    sink = torch.zeros(256 * 256, dtype=torch.float32, device="cuda")
+    gs.mfma_probe(dtype, gs.to_device(ones, dtype), sink, 10)
+    torch.cuda.synchronize()
+    assert torch.all(sink == 2048.0 * 10).item()
+    with pytest.raises(gs.GensorError):
+        gs.mfma_probe("f32", gs.to_device(np.ones(64 * 1024, dtype=np.float32), "f32"), sink, 10)
