@@ -44,10 +44,6 @@ def lattice():
         (256, 256, 32, 128, 128, 32, 1, 1),
         (128, 128, 32, 64, 64, 32, 1, 1),
         (128, 128, 128, 64, 64, 32, 1, 1),
-        # shallow k tile, eight waves: two workgroups fit a CU and cover each other's barriers and stores
-        (256, 128, 32, 64, 64, 32, 1, 1),
-        (128, 256, 32, 64, 64, 32, 1, 1),
-        (256, 256, 32, 64, 64, 32, 1, 1),
     ]
     for dt in ("f16", "bf16"):
         for bsrc in ("KC", "NC", "CONV"):
