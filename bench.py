@@ -272,6 +272,22 @@ def main():
             del c
             torch.cuda.empty_cache()
         line["operators"] = ops_out
+        # the paper's GEMM shapes with unbalanced dimensions (next in line after the five configurations)
+        nxt = []
+        for i in range(len(inputs.UNBALANCED_GEMMS)):
+            wl = inputs.unbalanced_gemm(i)
+            c = Case(gs, inputs, wl)
+            m = c.time_median_ms(max(5, min(steps2, int(20.0 / max(0.02, wl.flops / 1.0e12)))), 5)
+            tf = wl.flops / (m * 1e-3) / 1e12
+            nbytes = _algorithmic_bytes(wl, inputs)
+            ceiling = min(PEAK_TFLOPS[wl.dtype], wl.flops / nbytes * HBM_GBS / 1e3)
+            nxt.append({"workload": wl.name, "us": m * 1e3, "tflops": tf, "algorithmic_GBs": nbytes / (m * 1e-3) / 1e9,
+                        "roofline_ceiling_tflops": ceiling, "pct_of_roofline_ceiling": 100.0 * tf / ceiling,
+                        "kernel_id": c.sched.kernel_id, "construct_s": c.construct_s,
+                        "parity_rel_frobenius_sampled": c.parity(128)})
+            del c, wl
+            torch.cuda.empty_cache()
+        line["unbalanced_gemms"] = nxt
         line["cpu_baseline"] = cpu_baseline(w)
         line["paper_context"] = ("paper (RTX 4090, precision not stated): GEMM 45.2 TFLOP/s, Conv2d C1 34.54 TFLOP/s, "
                                  "construction 'a few seconds' (Table VI, Fig. 8 caption)")

@@ -458,7 +458,15 @@ extern "C" const gensor_hw* gensor_hw_mi355x(void) { return &kMi355x; }
 
 extern "C" gensor_status gensor_construct(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
                                           uint64_t seed, gensor_schedule* out) {
-  return construct_internal(p, hw, opts, seed, true, true, VIEW_DEFAULT, out);
+  // Operands are taken to be 16-byte aligned with dense leading dimensions; 16-byte vector
+  // accesses are then possible exactly when the contiguous extents are whole vectors.
+  GemmView v;
+  gensor_status st = gemm_view(p, &v, VIEW_DEFAULT);
+  if (st != GENSOR_OK) return st;
+  const int epc = 16 / v.esize;
+  bool vec_ok = true;
+  if (v.bsrc != B_CONV) vec_ok = v.K % epc == 0 && (v.bsrc == B_KC || v.N % epc == 0);
+  return construct_internal(p, hw, opts, seed, vec_ok, true, VIEW_DEFAULT, out);
 }
 
 extern "C" gensor_status gensor_construct_trace(const gensor_problem* p, const gensor_hw* hw,

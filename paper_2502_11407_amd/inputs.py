@@ -202,6 +202,18 @@ def config5_conv(which: str, n: int = 32, dtype: str = "f16", hw: int = 56) -> C
     return cw
 
 
+UNBALANCED_GEMMS = [(65536, 4, 1024), (32768, 64, 2048), (16384, 32, 1024), (65536, 1024, 4096), (8192, 8192, 8192)]
+
+
+def unbalanced_gemm(index: int, dtype: str = "f16") -> GemmWorkload:
+    """One of the paper's GEMM shapes with unbalanced dimensions, [M, K, N] as in its operator
+    table (GEMM rows) and its unbalanced-shape experiments; A and B row-major, uniform [-1, 1)."""
+    M, K, N = UNBALANCED_GEMMS[index]
+    return gemm_workload(f"gemm_{M}x{K}x{N}_{dtype}", dtype, M, N, K, 0, 0,
+                         lambda s: uniform_pm1(_seed(6 + index, 0), s, dtype),
+                         lambda s: uniform_pm1(_seed(6 + index, 1), s, dtype))
+
+
 def all_configs() -> Dict[str, object]:
     return {
         "cfg1": config1_gemm_f32(),

@@ -320,9 +320,12 @@ def test_cpp_cost_model_and_pick_equal_oracle():
             s = gs.instance_schedule(i.id, p)
             want = oc.predict_us(view, HW, i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn, i.vec, i.stages, i.direct)
             assert gs.predict_us(s, p) == want
+        # gensor_construct assumes aligned dense operands: vector accesses iff the contiguous extents are whole vectors
+        epc = 16 // view.e
+        vec_ok = view.bsrc == 2 or (view.K % epc == 0 and (view.bsrc == 0 or view.N % epc == 0))
         for seed in (0, 9):
             s = gs.construct(p, seed=seed)
-            got, us, scored = oc.construct(view, HW, OPTS, seed, insts)
+            got, us, scored = oc.construct(view, HW, OPTS, seed, insts, vec_ok)
             assert got is not None
             assert (s.kernel_id, s.predicted_us, s.states_scored) == (got.id, us, scored)
             assert s.chains == 1024 and 0 < s.iterations <= 100

@@ -316,9 +316,10 @@ def test_error_paths_launch_nothing(gs):
 
 # ------------------------------------------------------------------ full benchmark sizes
 def _full_size_case(gs, name):
-    """The benchmark workload `name` with the schedule bench.py would time (gensor_construct, seed 0)."""
+    """The benchmark workload `name` (or a workload object) with the schedule bench.py would time
+    (gensor_construct, seed 0)."""
     import torch
-    w = inputs.all_configs()[name]
+    w = inputs.all_configs()[name] if isinstance(name, str) else name
     if isinstance(w, inputs.GemmWorkload):
         p = gs.gemm_problem(w.dtype, w.M, w.N, w.K, w.transA, w.transB, w.batch)
         s = gs.construct(p, seed=0)
@@ -368,6 +369,17 @@ def test_benchmark_shapes_full_size_sampled(gs, name):
     assert err <= 2e-6
     scale = np.abs(want).max()
     assert np.abs(got - want).max() <= 1e-4 * scale
+
+
+@pytest.mark.parametrize("index", range(len(inputs.UNBALANCED_GEMMS)))
+def test_unbalanced_gemm_shapes_full_size_sampled(gs, index):
+    """The paper's GEMM shapes with unbalanced dimensions (K = 4 ... 8192) at full size with the
+    constructed schedule: sampled entries and tile edges against the oracle, nothing left unwritten."""
+    w, s, got, want, finite = _full_size_case(gs, inputs.unbalanced_gemm(index))
+    err = ops.rel_frobenius(got, want)
+    print(w.name, "kernel", s.kernel_id, "rel frobenius on samples", err)
+    assert finite
+    assert err <= 1e-5          # fp32 accumulation of up to 8192 exact products; the stated bound is 2e-3
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
