@@ -177,16 +177,16 @@ gensor_status gensor_bmm(const gensor_schedule* s, const gensor_problem* p, floa
  * (operator table, Conv2d row: O = (I * K) downsampled by S; cross-correlation, zero
  * padding; P = floor((h + 2 pad - r)/stride) + 1, Q likewise).  All three tensors are
  * contiguous.  Computed as an implicit GEMM: no im2col buffer is materialised.
- * Schedules that cache the input patch in LDS (direct_lds = 1) read a K,R,S,C copy of the
- * filters which the call first writes into `workspace` (device memory, 16-byte aligned,
- * at least gensor_workspace_bytes(s, p) bytes; GENSOR_ERR_WORKSPACE otherwise).  With
- * s == NULL such schedules are considered only if the workspace is large enough.
+ * Schedules that cache the input patch in LDS (direct_lds = 1) and the element-gather
+ * schedules use no workspace.
  * A pointwise convolution (r = s = 1, pad = 0) is one GEMM per image, O[n] = W * X[n] with
  * X[n][c][p*Q+q] = I[n][c][p*stride][q*stride]; gensor_construct and
  * gensor_instance_schedule treat it as that batched GEMM (m = k filters, n = P*Q, k = c).
  * With stride 1 the input itself is the B operand; with a larger stride the call first
- * compacts the sampled input into `workspace` (n*c*P*Q elements, same size rule and error
- * as above; with s == NULL and no such workspace the general implicit-GEMM path is used).
+ * compacts the sampled input into `workspace` (device memory, 16-byte aligned, at least
+ * gensor_workspace_bytes(s, p) = n*c*P*Q elements; GENSOR_ERR_WORKSPACE otherwise; with
+ * s == NULL and no such workspace the general implicit-GEMM path is used).  Stride 2 on rows
+ * of whole 16-byte vectors is sampled while the operand is fetched and needs none.
  * The workspace is scratch: its contents after the call are unspecified and nothing is
  * kept in it between calls.
  */

@@ -398,7 +398,7 @@ def predict_patch_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, stages) -> floa
     rows = (out_rows - 1) * stride + r + 2 * pad
     pw = w + 2 * pad
     stage = bm * (RS * bk * e + 16) + rows * pw * (bk * e + 16)
-    lds = stages * stage
+    lds = stages * stage + (0 if RS in (1, 9) else bm * RS * bk * e)        # + the raw filter runs
     if lds > hw.lds_bytes_per_cu:
         return -1.0
     nwaves = (bm // wm) * (bn // wn)
@@ -430,8 +430,7 @@ def predict_patch_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, stages) -> floa
     t_cu = rounds * (t_pro + nst * t_stage + t_epi)
     bytes_total = e * (n * c * h * w + view.M * view.K) + eo * view.M * view.N
     t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3)
-    # the filter pre-pass is a dependent launch of its own
-    return max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + 3.5 * hw.launch_us
+    return max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + hw.launch_us
 
 
 def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, direct) -> float:

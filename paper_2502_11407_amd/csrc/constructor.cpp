@@ -277,7 +277,7 @@ double predict_patch(const GemmView& v, const gensor_hw& hw, int bm, int bn, int
   const int64_t rows = ((int64_t)out_rows - 1) * v.cstride + v.cr + 2 * v.cpad;
   const int64_t pw = v.cw + 2 * v.cpad;
   const int64_t stage = (int64_t)bm * (RS * bk * e + 16) + rows * pw * (bk * e + 16);
-  const int64_t lds = stages * stage;
+  const int64_t lds = stages * stage + ((RS == 1 || RS == 9) ? 0 : (int64_t)bm * RS * bk * e);     // + the raw filter runs
   if (lds > hw.lds_bytes_per_cu) return -1.0;
   const int nwaves = (bm / wm) * (bn / wn);
   if (nwaves > hw.max_waves_per_wg) return -1.0;
@@ -311,8 +311,7 @@ double predict_patch(const GemmView& v, const gensor_hw& hw, int bm, int bn, int
   const double t_cu = rounds * (t_pro + nst * t_stage + t_epi);
   const double bytes_total = (double)(e * (v.cn * v.cc * v.ch * v.cw + v.M * v.K) + eo * v.M * v.N);
   const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3);
-  // the filter pre-pass is a dependent launch of its own
-  return (t_cu > t_hbm ? t_cu : t_hbm) + 0.3 * (t_cu > t_hbm ? t_hbm : t_cu) + 3.5 * hw.launch_us;
+  return (t_cu > t_hbm ? t_cu : t_hbm) + 0.3 * (t_cu > t_hbm ? t_hbm : t_cu) + hw.launch_us;
 }
 
 double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, int wm, int wn, int kg,
@@ -374,9 +373,8 @@ double predict_instance(const GemmView& v, const gensor_hw& hw, const InstanceDe
   return predict(v, hw, d.bm, d.bn, d.bk, d.wm, d.wn, d.kg, d.vm, d.vn, d.vec, d.stages, d.direct);
 }
 
-bool usable(const InstanceDesc& d, const GemmView& v, bool vec_ok, bool ws_ok = true) {
+bool usable(const InstanceDesc& d, const GemmView& v, bool vec_ok) {
   if (!instance_serves(d, v)) return false;
-  if (d.units && !ws_ok) return false;
   if (d.vec && !vec_ok) return false;
   if (d.direct && v.bsrc != B_CONV && v.K % d.bk != 0) return false;
   return true;
@@ -385,7 +383,7 @@ bool usable(const InstanceDesc& d, const GemmView& v, bool vec_ok, bool ws_ok = 
 }  // namespace
 
 gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
-                                 uint64_t seed, bool vec_ok, bool ws_ok, int view_mode, gensor_schedule* out) {
+                                 uint64_t seed, bool vec_ok, int view_mode, gensor_schedule* out) {
   if (!p || !out) return GENSOR_ERR_INVALID_ARG;
   const auto t0 = std::chrono::steady_clock::now();
   GemmView v;
@@ -415,7 +413,7 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
     for (int i = 0; i < g_num_instances; ++i) {
       const InstanceDesc& d = g_instances[i];
       if (d.bm != e.tile[0][0] || d.bn != e.tile[1][0] || d.wm != e.tile[0][1] || d.wn != e.tile[1][1]) continue;
-      if (!usable(d, v, vec_ok, ws_ok)) continue;
+      if (!usable(d, v, vec_ok)) continue;
       const double us = predict_instance(v, c.hw, d);
       if (us > 0 && (!best || us < best_us)) { best = &d; best_us = us; }
     }
@@ -430,7 +428,7 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
     double bd = 0.0;
     for (int i = 0; i < g_num_instances; ++i) {
       const InstanceDesc& d = g_instances[i];
-      if (!usable(d, v, vec_ok, ws_ok)) continue;
+      if (!usable(d, v, vec_ok)) continue;
       const double us = predict_instance(v, c.hw, d);
       if (us <= 0) continue;
       const int cand[8] = {d.bm, d.bn, d.bk, d.wm, d.wn, d.kg, d.vm, d.vn};
@@ -466,7 +464,7 @@ extern "C" gensor_status gensor_construct(const gensor_problem* p, const gensor_
   const int epc = 16 / v.esize;
   bool vec_ok = true;
   if (v.bsrc != B_CONV) vec_ok = v.K % epc == 0 && (v.bsrc == B_KC || v.N % epc == 0);
-  return construct_internal(p, hw, opts, seed, vec_ok, true, VIEW_DEFAULT, out);
+  return construct_internal(p, hw, opts, seed, vec_ok, VIEW_DEFAULT, out);
 }
 
 extern "C" gensor_status gensor_construct_trace(const gensor_problem* p, const gensor_hw* hw,

@@ -6,9 +6,11 @@
 // with the channel innermost.  One LDS stage holds BKC channels:
 //   * the filters of this workgroup's BM rows as a k-contiguous tile [BM][R*S*BKC] (row
 //     pitch an odd number of 16-byte chunks, so 16 consecutive rows fall in 16 different
-//     bank groups).  They are read from a copy of the filter tensor that a small pre-pass
-//     (permute_filters) has reordered from KCRS to K,R,S,C, so that BKC channels of one tap
-//     are contiguous;
+//     bank groups).  In the KCRS tensor the BKC channels x R*S taps of one filter are one
+//     contiguous run in (channel, tap) order, fetched with 16-byte vectors and reordered to
+//     (tap, channel): for 3x3 filters in registers (a thread holds the 9 vectors of one filter
+//     and channel group and byte-permutes them into 9 tile vectors), for 1x1 filters the two
+//     orders coincide, any other filter goes through a raw LDS region and element reads;
 //   * the input patch that the workgroup's BN output pixels touch, channel-last:
 //     [patch row][patch col][BKC channels + 16 bytes pad].  A patch row is a row of the
 //     zero-padded images stacked on top of each other; rows and columns outside an image are
@@ -40,27 +42,14 @@ struct ConvCfg {
   static constexpr int SLOT = BKC * ES + 16;           // bytes per patch pixel
   static constexpr int RS_MAX = 9;                     // taps supported by the staging registers
   static constexpr int A_VEC_MAX = (BM * BKC * RS_MAX / EPC + THREADS - 1) / THREADS;
+  static constexpr int U9_MAX = (BM * (BKC / EPC) + THREADS - 1) / THREADS;   // (filter, channel group) units per thread
+  static constexpr int A_REGS = A_VEC_MAX > 9 * U9_MAX ? A_VEC_MAX : 9 * U9_MAX;
   static constexpr int UNITS_MAX = UNITS_;             // patch transpose units per thread and stage
   static constexpr int LSTAGES = LSTAGES_;             // LDS buffers: 1 or 2
   static_assert(LSTAGES == 1 || LSTAGES == 2, "one or two LDS stages");
   static_assert(BKC % KG == 0 && KSTEPS_C >= 1, "channel tile must hold whole fragment k groups");
   static_assert(BM % WM == 0 && BN % WN == 0 && WM % MB == 0 && WN % MB == 0, "tiles");
 };
-
-// Filters KCRS -> K,R,S,C (element size ES bytes); one thread per output element.
-template <int ES>
-__global__ __launch_bounds__(256) void permute_filters(const void* w, void* out, int K, int Cc, int RS) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t total = (int64_t)K * Cc * RS;
-  if (i >= total) return;
-  const int c = (int)(i % Cc);
-  const int64_t t = i / Cc;
-  const int rs = (int)(t % RS);
-  const int64_t k = t / RS;
-  const int64_t src = (k * Cc + c) * RS + rs;
-  if constexpr (ES == 4) ((uint32_t*)out)[i] = ((const uint32_t*)w)[src];
-  else ((uint16_t*)out)[i] = ((const uint16_t*)w)[src];
-}
 
 // Input of a strided pointwise convolution, compacted: out[plane][p][q] = in[plane][p*stride][q*stride]
 // for plane = (image, channel).  16 / ES consecutive outputs per thread, one 16-byte store.
@@ -137,6 +126,8 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
   const int patch_rows = args.cPatchRows;
   const int stage_bytes = args.cStageBytes;
   const int a_bytes = BM * a_pitch;
+  const int raw_pitch = RS * BKC * ES;         // bytes of one filter's (channel, tap) run per stage; a multiple of 16
+  GENSOR_LDS char* raw = lds + C::LSTAGES * stage_bytes;   // raw filter runs, one buffer after the stages
   const int g_first = n0 / Q;                  // first stacked output row of this tile
   const int R0 = (g_first / P) * Hp + (g_first % P) * stride;   // first stacked padded input row
 
@@ -152,37 +143,126 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
 #pragma unroll
       for (int v = 0; v < MF::NACC; ++v) acc[i][j][v] = 0.f;
 
-  // ---- filter staging plan.  Vector v of this thread is one 16-byte channel group of one
-  // tap of one filter row in the K,R,S,C copy of the filters.
+  // ---- filter staging plan.  fmode 2 (3x3): unit u of this thread is one (filter row, channel
+  // group): 9 contiguous 16-byte pieces in, 9 tile vectors out, permuted in registers.
+  // fmode 1 (1x1) and 0 (other): vector v of this thread is, on the way in, the v-th 16-byte
+  // piece of a filter row's contiguous (channel, tap) run of this stage and, on the way out,
+  // one 16-byte channel group of one tap of a filter row of the tile.
+  const int fmode = RS == 9 ? 2 : (RS == 1 ? 1 : 0);
   const int a_vec_per_row = RS * C::OCT;
   const int a_vecs = BM * a_vec_per_row;
-  int a_goff[C::A_VEC_MAX];        // element offset at channel tile 0, or -1
-  int a_dst[C::A_VEC_MAX];         // LDS byte offset inside the filter tile
-  u32x4 a_reg[C::A_VEC_MAX];
+  constexpr int a_units = BM * C::OCT;
+  int a_goff[C::A_VEC_MAX];        // element offset of the piece (fmode 2: of the unit) at channel tile 0, or -1
+  u32x4 a_reg[C::A_REGS];
 #pragma unroll
   for (int v = 0; v < C::A_VEC_MAX; ++v) {
     const int q = tid + v * C::THREADS;
-    const int row = q / a_vec_per_row, t = q - row * a_vec_per_row;
-    const int rs = t / C::OCT, oct = t - rs * C::OCT;
-    const bool ok = q < a_vecs && (m0 + row) < args.M;
-    a_goff[v] = ok ? ((m0 + row) * RS + rs) * Cc + oct * EPC : -1;
-    a_dst[v] = row * a_pitch + t * 16;
+    if (fmode == 2) {
+      // units are dealt from the last thread down: the patch units start at thread 0, so the
+      // two kinds of loads land on different waves
+      const int qu = (C::THREADS - 1 - tid) + v * C::THREADS;
+      const int row = qu / C::OCT, oct = qu - row * C::OCT;
+      const bool ok = v < C::U9_MAX && qu < a_units && (m0 + row) < args.M;
+      a_goff[v] = ok ? ((m0 + row) * Cc + oct * EPC) * 9 : -1;
+    } else {
+      const int row = q / a_vec_per_row, t = q - row * a_vec_per_row;
+      const bool ok = q < a_vecs && (m0 + row) < args.M;
+      a_goff[v] = ok ? (m0 + row) * Cc * RS + t * EPC : -1;
+    }
   }
   auto fetch_a = [&](int c0) {
+    if (fmode == 2) {
 #pragma unroll
-    for (int v = 0; v < C::A_VEC_MAX; ++v) {
-      const int oct = (tid + v * C::THREADS) % C::OCT;
-      const bool ok = a_goff[v] >= 0 && c0 + oct * EPC < Cc;        // channel tail of the last stage reads zero
-      a_reg[v] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, ok ? (uint32_t)((a_goff[v] + c0) * ES) : OOB, 0, 0);
+      for (int u = 0; u < C::U9_MAX; ++u) {
+        const int oct = ((C::THREADS - 1 - tid) + u * C::THREADS) % C::OCT;
+        const bool ok = a_goff[u] >= 0 && c0 + oct * EPC < Cc;
+#pragma unroll
+        for (int i = 0; i < 9; ++i)
+          a_reg[u * 9 + i] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, ok ? (uint32_t)((a_goff[u] + c0 * 9 + i * EPC) * ES) : OOB, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int v = 0; v < C::A_VEC_MAX; ++v) {
+        // a piece starts at channel c0 + (t*EPC)/RS of the run; pieces are wholly inside or wholly
+        // beyond the channels that exist (C and the channel tile are multiples of EPC)
+        const int t = (tid + v * C::THREADS) % a_vec_per_row;
+        const bool ok = a_goff[v] >= 0 && c0 + (t * EPC) / RS < Cc;
+        a_reg[v] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, ok ? (uint32_t)((a_goff[v] + c0 * RS) * ES) : OOB, 0, 0);
+      }
     }
   };
-  auto commit_a = [&](int st) {
+  // fmode 2: element (channel c, tap rs) of a unit is element c*9 + rs of its 9 pieces
+  auto commit_a9 = [&](int st) {
+    GENSOR_LDS char* base = lds + st * stage_bytes;
+#pragma unroll
+    for (int u = 0; u < C::U9_MAX; ++u) {
+      const int q = (C::THREADS - 1 - tid) + u * C::THREADS;
+      if (q >= a_units) break;
+      const int row = q / C::OCT, oct = q - row * C::OCT;
+#pragma unroll
+      for (int rs = 0; rs < 9; ++rs) {
+        u32x4 o;
+        if constexpr (ES == 4) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) o[c] = a_reg[u * 9 + (c * 9 + rs) / 4][(c * 9 + rs) % 4];
+        } else {
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            const int e0 = (2 * d) * 9 + rs, e1 = (2 * d + 1) * 9 + rs;      // the two elements of dword d
+            const uint32_t lo = a_reg[u * 9 + e0 / 8][(e0 % 8) / 2], hi = a_reg[u * 9 + e1 / 8][(e1 % 8) / 2];
+            o[d] = __builtin_amdgcn_perm(hi, lo, ((e1 & 1) ? 0x07060000u : 0x05040000u) | ((e0 & 1) ? 0x0302u : 0x0100u));
+          }
+        }
+        *(GENSOR_LDS u32x4*)(base + row * a_pitch + (rs * C::OCT + oct) * 16) = o;
+      }
+    }
+  };
+  // fmode 1: the run is the tile row
+  auto commit_a1 = [&](int st) {
     GENSOR_LDS char* base = lds + st * stage_bytes;
 #pragma unroll
     for (int v = 0; v < C::A_VEC_MAX; ++v) {
-      if (tid + v * C::THREADS >= a_vecs) break;
-      *(GENSOR_LDS u32x4*)(base + a_dst[v]) = a_reg[v];
+      const int q = tid + v * C::THREADS;
+      if (q >= a_vecs) break;
+      const int row = q / a_vec_per_row, t = q - row * a_vec_per_row;
+      *(GENSOR_LDS u32x4*)(base + row * a_pitch + t * 16) = a_reg[v];
     }
+  };
+  auto commit_raw = [&]() {
+#pragma unroll
+    for (int v = 0; v < C::A_VEC_MAX; ++v) {
+      const int q = tid + v * C::THREADS;
+      if (q >= a_vecs) break;
+      *(GENSOR_LDS u32x4*)(raw + q * 16) = a_reg[v];      // row * raw_pitch + t * 16 = q * 16
+    }
+  };
+  // fmode 0: raw (channel, tap) runs -> tile rows in (tap, channel) order
+  auto permute_a = [&](int st) {
+    GENSOR_LDS char* base = lds + st * stage_bytes;
+#pragma unroll
+    for (int v = 0; v < C::A_VEC_MAX; ++v) {
+      const int q = tid + v * C::THREADS;
+      if (q >= a_vecs) break;
+      const int row = q / a_vec_per_row, t = q - row * a_vec_per_row;
+      const int rs = t / C::OCT, oct = t - rs * C::OCT;
+      GENSOR_LDS char* src = raw + row * raw_pitch + (oct * EPC * RS + rs) * ES;
+      u32x4 o;
+      if constexpr (ES == 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = *(GENSOR_LDS uint32_t*)(src + j * RS * 4);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          o[j] = (uint32_t)*(GENSOR_LDS uint16_t*)(src + (2 * j) * RS * 2) |
+                 ((uint32_t)*(GENSOR_LDS uint16_t*)(src + (2 * j + 1) * RS * 2) << 16);
+      }
+      *(GENSOR_LDS u32x4*)(base + row * a_pitch + t * 16) = o;
+    }
+  };
+  // filters of the fetched stage into tile `st`; with fmode 0 in two steps around a barrier
+  auto commit_a_direct = [&](int st) {
+    if (fmode == 2) commit_a9(st);
+    else if (fmode == 1) commit_a1(st);
   };
 
   // ---- patch staging plan.  A unit is EPC channels x EPC consecutive x of one patch row.
@@ -330,30 +410,35 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
     for (int st = 0; st < C::LSTAGES; ++st)
       for (int o = tid * 16; o < patch_bytes; o += C::THREADS * 16) *(GENSOR_LDS u32x4*)(lds + st * stage_bytes + a_bytes + o) = z;
   }
-  __syncthreads();
-  commit_a(0);
+  if (fmode == 0) {
+    commit_raw();
+    __syncthreads();
+    permute_a(0);
+  } else {
+    __syncthreads();                   // the zero fill before the first patch writes
+    commit_a_direct(0);
+  }
   commit_patch(0);
   __syncthreads();
   for (int st = 0; st < nstages; ++st) {
     const bool more = st + 1 < nstages;
+    const int cur = C::LSTAGES == 2 ? (st & 1) : 0, nxt = C::LSTAGES == 2 ? (cur ^ 1) : 0;
     if (more) {
       fetch_a((st + 1) * BKC);
       fetch_patch((st + 1) * BKC);
     }
-    if constexpr (C::LSTAGES == 2) {
-      compute(st & 1);
-      if (more) {
-        commit_a((st + 1) & 1);
-        commit_patch((st + 1) & 1);
-      }
-    } else {
-      // one buffer: every wave must have read this stage before the next one overwrites it;
-      // other workgroups on the CU fill the gap
-      compute(0);
-      if (more) {
-        __syncthreads();
-        commit_a(0);
-        commit_patch(0);
+    compute(cur);
+    if (more) {
+      if (fmode == 0) {
+        commit_raw();                  // the raw region is not read by compute
+        if constexpr (C::LSTAGES == 2) commit_patch(nxt);
+        __syncthreads();               // raw runs visible; with one stage: everyone has finished reading it
+        permute_a(nxt);
+        if constexpr (C::LSTAGES == 1) commit_patch(nxt);
+      } else {
+        if constexpr (C::LSTAGES == 1) __syncthreads();     // everyone has finished reading the single stage
+        commit_a_direct(nxt);
+        commit_patch(nxt);
       }
     }
     __syncthreads();

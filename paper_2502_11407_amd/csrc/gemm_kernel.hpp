@@ -52,7 +52,6 @@ struct KernelArgs {
   // patch-staged convolution only: images, LDS plan and tensor sizes in bytes (each < 2^31)
   int32_t cN, cApitch, cPatchRows, cStageBytes;
   int64_t cInBytes, cWBytes, cOutBytes;
-  void* cWorkspace;                // receives the permuted filters
 };
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));

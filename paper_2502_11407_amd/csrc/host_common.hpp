@@ -38,10 +38,9 @@ void schedule_from_instance(const InstanceDesc& d, gensor_schedule* s);
 bool instance_serves(const InstanceDesc& d, const GemmView& v);
 const InstanceDesc* find_instance(const gensor_schedule* s, const GemmView& v);
 
-// gensor_construct with three more inputs: whether the operands allow 16-byte vector accesses,
-// whether the caller supplied the workspace that patch-staged convolutions need, and the
-// view (ViewMode) a pointwise convolution is taken in.
+// gensor_construct with two more inputs: whether the operands allow 16-byte vector accesses
+// and the view (ViewMode) a pointwise convolution is taken in.
 gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,
-                                 uint64_t seed, bool vec_ok, bool ws_ok, int view_mode, gensor_schedule* out);
+                                 uint64_t seed, bool vec_ok, int view_mode, gensor_schedule* out);
 
 }  // namespace gensor

@@ -36,19 +36,10 @@ hipError_t launch_instance(const KernelArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-// patch-staged convolution: the LDS size depends on the problem (a.cStageBytes per LDS stage).
-// a.A is the caller's KCRS filter tensor and a.cWorkspace receives its K,R,S,C copy.
+// patch-staged convolution: the LDS size depends on the problem (a.cStageBytes per LDS stage
+// plus, unless the filter is 1x1 or 3x3, one raw filter region of BM * R*S*BKC elements).
 template <typename C>
-hipError_t launch_conv_instance(const KernelArgs& a0, hipStream_t st) {
-  KernelArgs a = a0;
-  {
-    const int64_t total = (int64_t)a.M * a.cC * a.cR * a.cS;
-    const unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(permute_filters<C::ES>, dim3(blocks), dim3(256), 0, st, a.A, a.cWorkspace, a.M, a.cC, a.cR * a.cS);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    a.A = a.cWorkspace;
-  }
+hipError_t launch_conv_instance(const KernelArgs& a, hipStream_t st) {
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)conv_patch_kernel<C>,
@@ -57,7 +48,9 @@ hipError_t launch_conv_instance(const KernelArgs& a0, hipStream_t st) {
     configured = true;
   }
   const unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n;
-  hipLaunchKernelGGL(conv_patch_kernel<C>, dim3(grid), dim3(C::THREADS), C::LSTAGES * a.cStageBytes, st, a);
+  const int rs = a.cR * a.cS;
+  const int raw_bytes = (rs == 1 || rs == 9) ? 0 : C::BM * rs * C::BKC * C::ES;   // those two reorder without it
+  hipLaunchKernelGGL(conv_patch_kernel<C>, dim3(grid), dim3(C::THREADS), C::LSTAGES * a.cStageBytes + raw_bytes, st, a);
   return hipGetLastError();
 }
 
