@@ -470,7 +470,7 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     scalar = 1.0 if vec else 6.0
     t_feed = scalar * e * kp * (bm + gather * bn) / l2_bw
     overlap = 0.7 + 0.1 * min(resident * nwaves / hw.simds_per_cu, 3.0)
-    if direct:
+    if direct and view.bsrc == 0:          # measured: direct staging pays for k-contiguous operands only
         overlap += 0.05
     # every k tile boundary (barrier, refill of the fragment pipeline) exposes a share of the memory latency
     t_ktile = 0.25 * hw.latency_ns[0] * 1e-3
@@ -478,7 +478,8 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units
     t_epi = bm * bn * eo / (0.8 * hbm_bw_cu)
     t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3
-    t_cu = cu_tiles * (t_main + t_epi / resident) + t_fill
+    # a second resident workgroup hides the stores of the first; further ones add nothing
+    t_cu = cu_tiles * (t_main + t_epi / min(resident, 2)) + t_fill
     bytes_total = view.batch * (e * (view.M * view.K + view.K * view.N) + eo * view.M * view.N)
     t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3)
     # soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)

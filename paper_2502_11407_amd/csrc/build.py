@@ -60,7 +60,7 @@ def generate():
         es = 4 if d["dt"] == "f32" else 2
         kg = (64 // d["mb"]) * (16 // es)
         a_bytes = d["bm"] * d["bk"] * es
-        b_bytes = d["bn"] * d["bk"] * es if d["bsrc"] == "KC" else d["bk"] * (d["bn"] * es + 32)
+        b_bytes = d["bn"] * d["bk"] * es if (d["bsrc"] == "KC" or d["direct"]) else d["bk"] * (d["bn"] * es + 32)
         lds = 0 if d["units"] else (a_bytes + b_bytes) * d["stages"]
         threads = (d["bm"] // d["wm"]) * (d["bn"] // d["wn"]) * 64
         reg.append("  {%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, launch_%d}," % (

@@ -351,7 +351,7 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   double par = resident * nwaves / hw.simds_per_cu;
   if (par > 3.0) par = 3.0;
   double overlap = 0.7 + 0.1 * par;
-  if (direct) overlap += 0.05;
+  if (direct && v.bsrc == B_KC) overlap += 0.05;      // measured: direct staging pays for k-contiguous operands only
   double t_main = t_mfma;
   if (t_lds > t_main) t_main = t_lds;
   if (t_feed > t_main) t_main = t_feed;
@@ -361,7 +361,8 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   const double hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units;
   const double t_epi = bm * bn * eo / (0.8 * hbm_bw_cu);
   const double t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3;
-  const double t_cu = cu_tiles * (t_main + t_epi / resident) + t_fill;
+  // a second resident workgroup hides the stores of the first; further ones add nothing
+  const double t_cu = cu_tiles * (t_main + t_epi / (resident < 2.0 ? resident : 2.0)) + t_fill;
   const double bytes_total = (double)v.batch * ((double)e * ((double)v.M * v.K + (double)v.K * v.N) + (double)eo * v.M * v.N);
   const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3);
   // soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)

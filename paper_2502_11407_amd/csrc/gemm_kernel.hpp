@@ -162,7 +162,10 @@ struct Cfg {
   static constexpr int CPR = PITCH_K / 16;                   // chunks per row
   static constexpr int RPP = (PITCH_K >= 256) ? 1 : 256 / PITCH_K;   // rows per 256-byte bank period
   // n-contiguous LDS tile: [BK][BN] + pad
-  static constexpr int PITCH_N = BN * ES + 32;
+  // (direct staging deposits whole 1 KB runs, so there the rows are unpadded and 32-byte
+  // column segments are XOR-swizzled with the k row instead)
+  static constexpr bool NC_DIRECT = DIRECT_ && BSRC_ == B_NC;
+  static constexpr int PITCH_N = NC_DIRECT ? BN * ES : BN * ES + 32;
   static constexpr int A_BYTES = BM * PITCH_K;
   static constexpr int B_BYTES = (BSRC == B_KC) ? BN * PITCH_K : BK * PITCH_N;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
@@ -176,12 +179,18 @@ struct Cfg {
   static_assert(BK % KG == 0, "BK must be a multiple of the fragment k extent");
   static_assert(MB == 32 || MB == 16, "MFMA block edge");
   static_assert(WAVES >= 1 && WAVES <= 16, "waves per workgroup");
-  static_assert(!DIRECT || (VEC && BSRC == B_KC), "direct-to-LDS needs vector loads of k-contiguous operands");
+  static_assert(!DIRECT || (VEC && (BSRC == B_KC || (BSRC == B_NC && BN * ES / 16 >= 16))),
+                "direct-to-LDS needs vector loads; an n-contiguous B needs rows of at least 16 chunks for its swizzle");
+  static_assert(!NC_DIRECT || (B_CHUNKS % THREADS == 0), "direct staging deposits whole waves");
   static_assert(BSRC != B_NCS2 || VEC, "the sampled source exists only with vector loads");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS capacity");
 };
 
 __device__ inline int swizzled_chunk(int row, int chunk, int rpp, int cpr) { return chunk ^ ((row / rpp) % cpr); }
+// Byte XOR applied inside an unpadded n-contiguous row of k row `krow`: the four rows a
+// 16-lane group of a transposing read touches land in four different 64-byte bank groups,
+// and rows 8 apart (the two groups of a 16x16-block read) in different 32-byte halves.
+__device__ inline int nc_swizzle(int krow) { return ((krow & 3) << 6) ^ (((krow >> 3) & 1) << 5); }
 
 // ---------------------------------------------------------------- the kernel
 template <typename C>
@@ -300,7 +309,9 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       b_kch[i] = krow;
     } else {
       constexpr int CPRN = BN * ES / 16;
-      const int krow = q / CPRN, ch = q % CPRN;
+      const int krow = q / CPRN;
+      int ch = q % CPRN;
+      if constexpr (C::NC_DIRECT) ch ^= nc_swizzle(krow) >> 4;      // slot q receives the chunk the swizzle maps there
       b_voff[i] = (uint32_t)((krow * (int)args.ldb + ch * EPC) * ES);
       b_kch[i] = krow;
     }
@@ -487,7 +498,11 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         u32x4 v;
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt)
-          v[tt] = *(GENSOR_LDS uint32_t*)(bbase + (ks * C::KG + fgrp * 4 + tt) * C::PITCH_N + col * 4);
+        {
+          const int kr = ks * C::KG + fgrp * 4 + tt;
+          const int cb = C::NC_DIRECT ? ((col * 4) ^ nc_swizzle(kr)) : col * 4;
+          v[tt] = *(GENSOR_LDS uint32_t*)(bbase + kr * C::PITCH_N + cb);
+        }
         fb[buf][bj] = v;
       } else {
         // 16-bit, [k][n] tile: two transposing reads.  In each 16-lane group, lane s
@@ -502,9 +517,11 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
           krow = ks * C::KG + g * 8 + (s >> 2);
           col = block_col(bj) + (s & 3) * 4;
         }
-        GENSOR_LDS char* p = bbase + krow * C::PITCH_N + col * 2;
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)p);
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + 4 * C::PITCH_N));
+        const int cb0 = C::NC_DIRECT ? ((col * 2) ^ nc_swizzle(krow)) : col * 2;
+        const int cb1 = C::NC_DIRECT ? ((col * 2) ^ nc_swizzle(krow + 4)) : col * 2;
+        GENSOR_LDS char* p = bbase + krow * C::PITCH_N;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + cb0));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + 4 * C::PITCH_N + cb1));
         u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
         u32x4 v = {l2[0], l2[1], h2[0], h2[1]};
         fb[buf][bj] = v;

@@ -59,6 +59,10 @@ def lattice():
         for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles16:
             if bm * bn >= 128 * 128:
                 out.append(_inst(dt, "f32", bm, bn, bk, wm, wn, mb, vm, vn, "KC", direct=1))
+        # the same for an n-contiguous B (rows of at least 16 chunks: its swizzle needs them)
+        for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles16:
+            if bm * bn >= 128 * 128 and bn >= 128:
+                out.append(_inst(dt, "f32", bm, bn, bk, wm, wn, mb, vm, vn, "NC", direct=1))
         # 16-bit output variants
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "KC"))
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "NC"))
