@@ -3,6 +3,9 @@
 // staging mode, vector width) for one element type and operand source.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <atomic>
+
 #include "conv_kernel.hpp"
 #include "gemm_kernel.hpp"
 
@@ -22,15 +25,26 @@ struct InstanceDesc {
 extern const InstanceDesc g_instances[];
 extern const int g_num_instances;
 
+// The dynamic-LDS limit of a kernel is a per-device attribute: set it once on every device
+// the instance is launched on (one bit per device ordinal; thread-safe, setting twice is harmless).
+template <typename K>
+hipError_t allow_dynamic_lds(K kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) return e;
+  done.fetch_or(bit, std::memory_order_release);
+  return hipSuccess;
+}
+
 template <typename C>
 hipError_t launch_instance(const KernelArgs& a, hipStream_t st) {
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)contraction_kernel<C>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::atomic<uint64_t> done{0};
+  hipError_t e = allow_dynamic_lds(contraction_kernel<C>, C::LDS_BYTES, done);
+  if (e != hipSuccess) return e;
   const unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.batch;
   hipLaunchKernelGGL(contraction_kernel<C>, dim3(grid), dim3(C::THREADS), C::LDS_BYTES, st, a);
   return hipGetLastError();
@@ -40,13 +54,9 @@ hipError_t launch_instance(const KernelArgs& a, hipStream_t st) {
 // plus, unless the filter is 1x1 or 3x3, one raw filter region of BM * R*S*BKC elements).
 template <typename C>
 hipError_t launch_conv_instance(const KernelArgs& a, hipStream_t st) {
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)conv_patch_kernel<C>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::atomic<uint64_t> done{0};
+  hipError_t e = allow_dynamic_lds(conv_patch_kernel<C>, 160 * 1024, done);
+  if (e != hipSuccess) return e;
   const unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n;
   const int rs = a.cR * a.cS;
   const int raw_bytes = (rs == 1 || rs == 9) ? 0 : C::BM * rs * C::BKC * C::ES;   // those two reorder without it
