@@ -34,6 +34,9 @@ def lib():
         L.oracle_conv2d.argtypes = [i32] + [i64] * 9 + [ptr, ptr, ptr]
         L.oracle_conv2d_at.restype = i32
         L.oracle_conv2d_at.argtypes = [i32] + [i64] * 9 + [ptr, ptr, i64, ptr, ptr]
+        L.oracle_gemv.argtypes = [i32, i64, i64, dbl, ptr, i64, ptr, dbl, ptr]
+        L.oracle_avgpool2d.argtypes = [i32] + [i64] * 6 + [ptr, ptr]
+        L.oracle_avgpool2d_at.argtypes = [i32] + [i64] * 5 + [ptr, i64, ptr, ptr]
         _lib = L
     return _lib
 
@@ -135,6 +138,42 @@ def conv2d_at(I, W, dtype, coords, stride=1, pad=0):
     out = np.zeros(co.shape[0], dtype=np.float64)
     rc = lib().oracle_conv2d_at(_DT[dtype], n, c, h, w, k, r, s, stride, pad, _p(I), _p(W),
                                 co.shape[0], _p(co), _p(out))
+    assert rc == 0
+    return out
+
+
+def gemv(A, x, dtype, alpha=1.0, beta=0.0, y0=None):
+    """y = alpha A x + beta y0 for a row-major A [M][N] (GEMV row of the operator table)."""
+    A = _check(A, dtype)
+    x = _check(x, dtype)
+    M, N = A.shape
+    assert x.shape == (N,)
+    y = np.zeros(M, dtype=np.float64) if y0 is None else np.array(y0, dtype=np.float64)
+    rc = lib().oracle_gemv(_DT[dtype], M, N, float(alpha), _p(A), N, _p(x), float(beta), _p(y))
+    assert rc == 0
+    return y
+
+
+def pool_out_shape(n, c, h, w, f, stride):
+    return (n, c, (h - f) // stride + 1, (w - f) // stride + 1)
+
+
+def avgpool2d(I, dtype, f, stride):
+    """O = average over f x f windows at the given stride of an NCHW input, no padding."""
+    I = _check(I, dtype)
+    n, c, h, w = I.shape
+    O = np.zeros(pool_out_shape(n, c, h, w, f, stride), dtype=np.float64)
+    rc = lib().oracle_avgpool2d(_DT[dtype], n, c, h, w, f, stride, _p(I), _p(O))
+    assert rc == 0
+    return O
+
+
+def avgpool2d_at(I, dtype, coords, f, stride):
+    I = _check(I, dtype)
+    n, c, h, w = I.shape
+    co = np.ascontiguousarray(coords, dtype=np.int64)
+    out = np.zeros(co.shape[0], dtype=np.float64)
+    rc = lib().oracle_avgpool2d_at(_DT[dtype], c, h, w, f, stride, _p(I), co.shape[0], _p(co), _p(out))
     assert rc == 0
     return out
 

@@ -1,5 +1,6 @@
 /*
- * CPU oracle for the dense operators: GEMM, batched matmul and 2-D convolution.
+ * CPU oracle for the operators: GEMM, batched matmul, 2-D convolution, GEMV and 2-D
+ * average pooling.
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition of what the GPU
  * kernels must compute; it shares no code with them.  Only tests, the smoke check and
@@ -11,6 +12,8 @@
  *   Conv2d O = (I * K) downsampled by S on NCHW input and KCRS filters, read as a
  *          cross-correlation (no filter flip) with explicit symmetric zero padding
  *          (operator table, Conv2d row)
+ *   GEMV   y_i = alpha * sum_n A_in x_n + beta * y_i             (operator table, GEMV row)
+ *   AvgPooling2d  O_xy = (1/F^2) sum_ij I_{S x + i, S y + j}      (operator table, AvgPooling2d row)
  * Inputs are decoded from their stored bits (fp32, IEEE half, bfloat16) to double
  * exactly; products and sums are carried in double, in index order.  There is no
  * blocking, no reordering and no library call.  OpenMP only splits the outermost
@@ -201,5 +204,64 @@ int oracle_conv2d_at(int dtype, int64_t N, int64_t C, int64_t H, int64_t W,
     for (int64_t t = 0; t < count; ++t)
         out[t] = conv_entry(dtype, C, H, W, R, S, stride, pad, I, Wt,
                             nkpq[4 * t], nkpq[4 * t + 1], nkpq[4 * t + 2], nkpq[4 * t + 3]);
+    return 0;
+}
+
+/*
+ * GEMV: y_i = alpha * sum_n A_in x_n + beta * y_i, i in [0, M)   (operator table, GEMV row).
+ * A is row-major with leading dimension lda; one serial double sum per output, in index
+ * order.  y holds the prior values on entry (read only if beta != 0) and the result on exit.
+ */
+int oracle_gemv(int dtype, int64_t M, int64_t N, double alpha, const void *A, int64_t lda,
+                const void *x, double beta, double *y)
+{
+    if (dtype < 0 || dtype > 2 || M < 0 || N < 0 || lda < N) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        double acc = 0.0;
+        for (int64_t n = 0; n < N; ++n)
+            acc += oracle_decode(dtype, A, i * lda + n) * oracle_decode(dtype, x, n);
+        y[i] = alpha * acc + (beta != 0.0 ? beta * y[i] : 0.0);
+    }
+    return 0;
+}
+
+/*
+ * AvgPooling2d: O[n][c][x][y] = (1/F^2) * sum_{i<F} sum_{j<F} I[n][c][S*x + i][S*y + j]
+ * (operator table, AvgPooling2d row) on an NCHW input, no padding; the output extent is
+ * floor((H - F)/S) + 1 by floor((W - F)/S) + 1 (windows that would leave the image do not
+ * exist).  The window is summed in double in (i, j) order, then divided once by F*F.
+ */
+static double pool_entry(int dtype, int64_t H, int64_t W, int64_t F, int64_t S, const void *I,
+                         int64_t plane, int64_t p, int64_t q)
+{
+    double acc = 0.0;
+    for (int64_t i = 0; i < F; ++i)
+        for (int64_t j = 0; j < F; ++j)
+            acc += oracle_decode(dtype, I, (plane * H + S * p + i) * W + S * q + j);
+    return acc / (double)(F * F);
+}
+
+int oracle_avgpool2d(int dtype, int64_t N, int64_t C, int64_t H, int64_t W, int64_t F, int64_t S,
+                     const void *I, double *O)
+{
+    if (dtype < 0 || dtype > 2 || F < 1 || S < 1 || H < F || W < F) return 1;
+    int64_t P = (H - F) / S + 1, Q = (W - F) / S + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t plane = 0; plane < N * C; ++plane)
+        for (int64_t p = 0; p < P; ++p)
+            for (int64_t q = 0; q < Q; ++q)
+                O[(plane * P + p) * Q + q] = pool_entry(dtype, H, W, F, S, I, plane, p, q);
+    return 0;
+}
+
+/* The same for `count` output coordinates (n, c, p, q) given as a flat int64 array. */
+int oracle_avgpool2d_at(int dtype, int64_t C, int64_t H, int64_t W, int64_t F, int64_t S,
+                        const void *I, int64_t count, const int64_t *ncpq, double *out)
+{
+    if (dtype < 0 || dtype > 2 || F < 1 || S < 1 || H < F || W < F) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < count; ++t)
+        out[t] = pool_entry(dtype, H, W, F, S, I, ncpq[4 * t] * C + ncpq[4 * t + 1], ncpq[4 * t + 2], ncpq[4 * t + 3]);
     return 0;
 }

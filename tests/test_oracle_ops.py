@@ -274,3 +274,83 @@ def test_seeded_inputs_are_reproducible_and_shaped():
     c = inputs.config5_conv("1x1s2", n=1, hw=8)
     assert c.W.shape == (512, 256, 1, 1) and c.stride == 2 and c.pad == 0
     assert abs(float(a.A.astype(np.float32).max())) <= 1.0
+
+
+# ------------------------------------------------------------------ GEMV (operator table, GEMV row)
+def test_gemv_hand_case_and_scalars():
+    # [[1,2,3],[4,5,6]] . [1,0,-1] = [-2,-2]
+    A = np.array([[1, 2, 3], [4, 5, 6]], dtype=np.float32)
+    x = np.array([1, 0, -1], dtype=np.float32)
+    assert ops.gemv(A, x, "f32").tolist() == [-2.0, -2.0]
+    assert ops.gemv(A, x, "f32", alpha=3.0, beta=0.5, y0=[10.0, 20.0]).tolist() == [-1.0, 4.0]
+    assert ops.gemv(A, x, "f32", alpha=0.0, beta=1.0, y0=[7.0, -9.0]).tolist() == [7.0, -9.0]
+    # beta = 0 must not read y0
+    assert ops.gemv(A, x, "f32", beta=0.0, y0=[np.nan, np.nan]).tolist() == [-2.0, -2.0]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_gemv_against_numpy_and_gemm(dtype):
+    A = inputs.small_ints(31, (37, 53), dtype)
+    x = inputs.small_ints(32, (53,), dtype)
+    got = ops.gemv(A, x, dtype)
+    want = ops.decode(A, dtype) @ ops.decode(x, dtype)                  # float64 library matmul
+    assert np.array_equal(got, want)
+    # a GEMV is the GEMM with a single column (the two oracle routines share only the decoder)
+    assert np.array_equal(got, ops.gemm(A, x.reshape(53, 1), dtype)[:, 0])
+    # unit vectors pick columns (a transposed A or a wrong stride would pick rows)
+    for n in (0, 17, 52):
+        e = np.zeros(53, dtype=np.float32)
+        e[n] = 1.0
+        assert np.array_equal(ops.gemv(A, inputs.to_storage(e, dtype), dtype), ops.decode(A, dtype)[:, n])
+
+
+def test_gemv_real_values_close_to_longdouble():
+    A = inputs.uniform_pm1(33, (64, 1000), "f16")
+    x = inputs.uniform_pm1(34, (1000,), "f16")
+    want = (A.astype(np.longdouble) * x.astype(np.longdouble)[None, :]).sum(axis=1)
+    assert np.abs(ops.gemv(A, x, "f16") - want.astype(np.float64)).max() <= 1e-12
+
+
+# ------------------------------------------------------------------ AvgPooling2d (operator table, AvgPooling2d row)
+def test_avgpool_hand_case():
+    I = np.arange(16, dtype=np.float32).reshape(1, 1, 4, 4)
+    # 2x2 windows at stride 2: means of {0,1,4,5}, {2,3,6,7}, {8,9,12,13}, {10,11,14,15}
+    assert ops.avgpool2d(I, "f32", 2, 2).reshape(-1).tolist() == [2.5, 4.5, 10.5, 12.5]
+    # 3x3 window at stride 1 on the same image: centre values 5, 6, 9, 10 (mean of a ramp = its centre)
+    assert ops.avgpool2d(I, "f32", 3, 1).reshape(-1).tolist() == [5.0, 6.0, 9.0, 10.0]
+    # a window that would leave the image does not exist: 4 -> floor((4-3)/2)+1 = 1
+    assert ops.avgpool2d(I, "f32", 3, 2).shape == (1, 1, 1, 1)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("f,stride,h,w", [(2, 2, 8, 10), (3, 2, 9, 7), (2, 2, 7, 9), (3, 1, 6, 6), (1, 3, 7, 8)])
+def test_avgpool_against_numpy_windows(dtype, f, stride, h, w):
+    I = inputs.small_ints(35, (2, 3, h, w), dtype, -8, 8)
+    got = ops.avgpool2d(I, dtype, f, stride)
+    d = ops.decode(I, dtype)
+    P, Q = (h - f) // stride + 1, (w - f) // stride + 1
+    assert got.shape == (2, 3, P, Q)
+    # sliding_window_view is numpy's own windowing; mean over the window axes
+    win = np.lib.stride_tricks.sliding_window_view(d, (f, f), axis=(2, 3))[:, :, ::stride, ::stride]
+    assert np.array_equal(got, win.sum(axis=(4, 5)) / (f * f))
+    # coordinates one by one
+    co = np.array([[0, 0, 0, 0], [1, 2, P - 1, Q - 1], [1, 0, P // 2, 0]], dtype=np.int64)
+    assert np.array_equal(ops.avgpool2d_at(I, dtype, co, f, stride), got[co[:, 0], co[:, 1], co[:, 2], co[:, 3]])
+
+
+def test_avgpool_closed_forms_and_conv_identity():
+    # constant image -> the constant; delta at (y0, x0) -> 1/F^2 in exactly the windows that hold it
+    I = np.full((1, 2, 9, 9), 3.0, dtype=np.float32)
+    assert np.all(ops.avgpool2d(I, "f32", 3, 2) == 3.0)
+    D = np.zeros((1, 1, 9, 9), dtype=np.float32)
+    D[0, 0, 4, 5] = 9.0
+    O = ops.avgpool2d(D, "f32", 3, 2)                          # windows start at 0,2,4,6: rows {2,4} cols {4} hold (4,5)
+    want = np.zeros((1, 1, 4, 4))
+    want[0, 0, 1, 2] = want[0, 0, 2, 2] = 1.0
+    assert np.array_equal(O, want)
+    # pooling is the convolution with a constant 1/F^2 filter per channel
+    X = inputs.small_ints(36, (2, 3, 8, 8), "f32", -8, 8)
+    Wt = np.zeros((3, 3, 2, 2), dtype=np.float32)
+    for c in range(3):
+        Wt[c, c] = 0.25
+    assert np.array_equal(ops.avgpool2d(X, "f32", 2, 2), ops.conv2d(X, Wt, "f32", stride=2, pad=0))
