@@ -170,6 +170,72 @@ def mfma_ceiling(gs, inputs, dtype, iters=20000):
     return flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
+def _median_ms(fn, steps, warmup=5, batches=5):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    out = []
+    for _ in range(batches):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out.append(e0.elapsed_time(e1) / steps)
+    return sorted(out)[len(out) // 2]
+
+
+def operator_table_rows(gs, inputs):
+    """The other shapes of the paper's operator table: Conv2d C1-C3 (constructed schedules), GEMV V1-V3 and
+    AvgPooling2d P1-P3 (streaming kernels, judged against HBM bandwidth)."""
+    import torch
+    from oracle import ops
+    rows = []
+    for i in range(len(inputs.PAPER_CONVS)):
+        wl = inputs.paper_conv(i)
+        c = Case(gs, inputs, wl)
+        m = c.time_median_ms(30, 5)
+        nbytes = _algorithmic_bytes(wl, inputs)
+        tf = wl.flops / (m * 1e-3) / 1e12
+        ceiling = min(PEAK_TFLOPS[wl.dtype], wl.flops / nbytes * HBM_GBS / 1e3)
+        rows.append({"workload": wl.name, "us": m * 1e3, "tflops": tf, "algorithmic_GBs": nbytes / (m * 1e-3) / 1e9,
+                     "pct_of_roofline_ceiling": 100.0 * tf / ceiling, "kernel_id": c.sched.kernel_id,
+                     "parity_rel_frobenius_sampled": c.parity(128)})
+        del c, wl
+        torch.cuda.empty_cache()
+    for i, (M, N) in enumerate(inputs.GEMV_SHAPES):
+        A, x = inputs.gemv_workload(i)
+        dA, dx = gs.to_device(A, "f16"), gs.to_device(x, "f16")
+        y = torch.empty(M, dtype=torch.float32, device="cuda")
+        m = _median_ms(lambda: gs.gemv("f16", dA, dx, y), 30)
+        nbytes = 2 * (M * N + N) + 4 * M
+        sel = inputs.sample_indices(7, (M,), 64)[:, 0]
+        err = ops.rel_frobenius(gs.to_host_f64(y)[sel], ops.gemv(np.ascontiguousarray(A[sel]), x, "f16"))
+        rows.append({"workload": f"gemv_{M}x{N}_f16", "us": m * 1e3, "tflops": 2.0 * M * N / (m * 1e-3) / 1e12,
+                     "algorithmic_GBs": nbytes / (m * 1e-3) / 1e9, "pct_of_hbm_peak": 100.0 * nbytes / (m * 1e-3) / 1e9 / HBM_GBS,
+                     "parity_rel_frobenius_sampled": err})
+        del dA, dx, A
+        torch.cuda.empty_cache()
+    for i in range(len(inputs.POOL_SHAPES)):
+        I, f, stride = inputs.pool_workload(i)
+        shape = ops.pool_out_shape(*I.shape, f, stride)
+        dI = gs.to_device(I, "f16")
+        O = gs.empty_device(shape)
+        m = _median_ms(lambda: gs.avgpool2d("f16", dI, O, f, stride), 30)
+        nbytes = 2 * I.size + 4 * int(np.prod(shape))
+        co = inputs.sample_indices(7, shape, 256)
+        idx = torch.from_numpy(co).cuda()
+        got = O[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].double().cpu().numpy()
+        rows.append({"workload": "avgpool_%dx%dx%dx%d_f%d_s%d_f16" % (*I.shape, f, stride), "us": m * 1e3,
+                     "algorithmic_GBs": nbytes / (m * 1e-3) / 1e9, "pct_of_hbm_peak": 100.0 * nbytes / (m * 1e-3) / 1e9 / HBM_GBS,
+                     "parity_rel_frobenius_sampled": ops.rel_frobenius(got, ops.avgpool2d_at(I, "f16", co, f, stride))})
+        del dI, O, I
+        torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(w):
     """The oracle as it stands on a bounded slice (leading rows of A) of the headline GEMM."""
     from oracle import ops
@@ -288,6 +354,7 @@ def main():
             del c, wl
             torch.cuda.empty_cache()
         line["unbalanced_gemms"] = nxt
+        line["operator_table"] = operator_table_rows(gs, inputs)
         line["cpu_baseline"] = cpu_baseline(w)
         line["paper_context"] = ("paper (RTX 4090, precision not stated): GEMM 45.2 TFLOP/s, Conv2d C1 34.54 TFLOP/s, "
                                  "construction 'a few seconds' (Table VI, Fig. 8 caption)")

@@ -197,6 +197,31 @@ gensor_status gensor_conv2d(const gensor_schedule* s, const gensor_problem* p,
 size_t gensor_workspace_bytes(const gensor_schedule* s, const gensor_problem* p);
 
 /*
+ * y[i] = alpha * sum_{n<N} A[i][n] * x[n] + beta * y[i], i < M   (operator table, GEMV row).
+ * A is row-major [M][lda] (lda >= N, in elements) and x has N elements, both of in_dtype on
+ * the device; y is fp32 on the device and is read only if beta != 0.  Products and sums are
+ * carried in fp32.  A memory-bound streaming kernel with a fixed internal schedule (no
+ * gensor_schedule): 16-byte vector loads when A and x are 16-byte aligned and lda is a whole
+ * number of vectors, element loads otherwise.  Enqueued on hip_stream; nothing is allocated.
+ * INVALID_ARG for null pointers, non-positive extents or lda < N.
+ */
+gensor_status gensor_gemv(gensor_dtype in_dtype, int64_t M, int64_t N, float alpha,
+                          const void* A, int64_t lda, const void* x, float beta, float* y,
+                          void* hip_stream);
+
+/*
+ * O[n][c][p][q] = (1 / f^2) * sum_{i<f} sum_{j<f} I[n][c][stride*p + i][stride*q + j]
+ * (operator table, AvgPooling2d row) on a contiguous NCHW input, no padding;
+ * P = floor((h - f)/stride) + 1, Q likewise.  The window is summed in fp32 and divided once.
+ * out_dtype is GENSOR_F32 or in_dtype (round to nearest even).  Memory-bound streaming
+ * kernel, fixed internal schedule, enqueued on hip_stream, nothing allocated.
+ * INVALID_ARG for null pointers, non-positive extents or f larger than the image.
+ */
+gensor_status gensor_avgpool2d(gensor_dtype in_dtype, gensor_dtype out_dtype,
+                               int64_t n, int64_t c, int64_t h, int64_t w, int64_t f, int64_t stride,
+                               const void* input, void* output, void* hip_stream);
+
+/*
  * Measurement aid, not an operator: launches a kernel of nothing but dense 16-bit MFMAs
  * (one workgroup of 4 wavefronts per CU, 8 independent 32x32 accumulators per wavefront,
  * `iters` rounds of 8 instructions) whose A and B fragments are loaded once from

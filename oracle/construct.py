@@ -466,7 +466,7 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     lds_bw = hw.bandwidth_gbs[1] * 1e3 / hw.compute_units                                     # bytes/us per CU
     t_lds = e * kp * (bm * (bn // wn) + bn * (bm // wm) + (bm + bn)) / lds_bw
     l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units
-    gather = 4.0 if (view.bsrc == 2 and not direct) else 1.0
+    gather = 16.0 if (view.bsrc == 2 and not direct) else 1.0     # element-wise loads and their index arithmetic
     scalar = 1.0 if vec else 6.0
     t_feed = scalar * e * kp * (bm + gather * bn) / l2_bw
     overlap = 0.7 + 0.1 * min(resident * nwaves / hw.simds_per_cu, 3.0)

@@ -23,7 +23,7 @@ OP_GEMM, OP_BMM, OP_CONV2D = 0, 1, 2
 
 EXPORTS = ["gensor_hw_mi355x", "gensor_construct", "gensor_construct_trace", "gensor_predict_us",
            "gensor_num_instances", "gensor_instance_schedule", "gensor_gemm", "gensor_bmm", "gensor_conv2d",
-           "gensor_workspace_bytes", "gensor_status_string", "gensor_mfma_probe"]
+           "gensor_workspace_bytes", "gensor_status_string", "gensor_mfma_probe", "gensor_gemv", "gensor_avgpool2d"]
 
 
 class Problem(C.Structure):
@@ -101,6 +101,10 @@ def _load():
     L.gensor_conv2d.argtypes = [S, P, vp, vp, vp, vp, C.c_size_t, vp]
     L.gensor_workspace_bytes.restype = C.c_size_t
     L.gensor_workspace_bytes.argtypes = [S, P]
+    L.gensor_gemv.restype = i32
+    L.gensor_gemv.argtypes = [i32, i64, i64, f32, vp, i64, vp, f32, vp, vp]
+    L.gensor_avgpool2d.restype = i32
+    L.gensor_avgpool2d.argtypes = [i32, i32, i64, i64, i64, i64, i64, i64, vp, vp, vp]
     L.gensor_mfma_probe.restype = i32
     L.gensor_mfma_probe.argtypes = [i32, vp, vp, i32, vp]
     return L
@@ -230,6 +234,22 @@ def to_device(arr: np.ndarray, dtype: str):
     if dtype == "bf16":
         return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).cuda().view(torch.bfloat16)
     return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+
+def gemv(dtype: str, A, x, y, alpha: float = 1.0, beta: float = 0.0, lda: Optional[int] = None, stream=None):
+    """y = alpha A x + beta y: A [M][N] row-major and x [N] of `dtype`, y [M] fp32, all on the device."""
+    M, N = A.shape
+    st = lib.gensor_gemv(DTYPE[dtype], M, N, alpha, A.data_ptr(), lda if lda is not None else A.stride(0), x.data_ptr(),
+                         beta, y.data_ptr(), _stream_ptr(stream))
+    _check(st, "gensor_gemv")
+
+
+def avgpool2d(dtype: str, I, O, f: int, stride: int, out_dtype: str = "f32", stream=None):
+    """O = f x f average pooling at `stride` of a contiguous NCHW device tensor."""
+    n, c, h, w = I.shape
+    st = lib.gensor_avgpool2d(DTYPE[dtype], DTYPE[out_dtype], n, c, h, w, f, stride, I.data_ptr(), O.data_ptr(),
+                              _stream_ptr(stream))
+    _check(st, "gensor_avgpool2d")
 
 
 def mfma_probe(dtype: str, operands, sink, iters: int, stream=None):

@@ -99,7 +99,7 @@ def _compile(src):
 
 def build(force=False, jobs=None):
     tus = generate()
-    tus += [os.path.join(HERE, "gensor_api.cpp"), os.path.join(HERE, "constructor.cpp"), os.path.join(HERE, "probe.cpp")]
+    tus += [os.path.join(HERE, "gensor_api.cpp"), os.path.join(HERE, "constructor.cpp"), os.path.join(HERE, "probe.cpp"), os.path.join(HERE, "scan_kernels.cpp")]
     if force:
         for f in os.listdir(GEN):
             if f.endswith(".o"):

@@ -345,7 +345,7 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   const double lds_bw = hw.bandwidth_gbs[1] * 1e3 / hw.compute_units;
   const double t_lds = e * kp * (bm * (bn / wn) + bn * (bm / wm) + (bm + bn)) / lds_bw;
   const double l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units;
-  const double gather = (v.bsrc == B_CONV && !direct) ? 4.0 : 1.0;
+  const double gather = (v.bsrc == B_CONV && !direct) ? 16.0 : 1.0;     // element-wise loads and their index arithmetic
   const double scalar = vec ? 1.0 : 6.0;
   const double t_feed = scalar * e * kp * (bm + gather * bn) / l2_bw;
   double par = resident * nwaves / hw.simds_per_cu;

@@ -1,0 +1,212 @@
+// The two memory-bound operators of the paper's benchmark: GEMV and AvgPooling2d (operator
+// table, GEMV and AvgPooling2d rows).  Neither is a contraction worth a matrix core: both
+// stream their input once from HBM, so the kernels are plain coalesced vector loads, fp32
+// arithmetic on the vector ALUs and one store per output.
+#include <hip/hip_runtime.h>
+
+#include "../../include/gensor.h"
+#include "gemm_kernel.hpp"
+
+namespace gensor {
+
+// 16 bytes of stored elements -> fp32 values
+template <typename T>
+__device__ inline void unpack_chunk(const u32x4& v, float* f) {
+  if constexpr (ElemSize<T>::value == 4) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) f[e] = as_f32(v[e]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint16_t bits = (uint16_t)(v[e >> 1] >> ((e & 1) * 16));
+      f[e] = to_float<T>(&bits, 0);
+    }
+  }
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMV, y_i = alpha * sum_n A_in x_n + beta * y_i.  A workgroup of 4 waves owns 8 rows (two
+// per wave, so every x vector read from LDS is used twice); x is staged through LDS in
+// panels of PANEL elements; a lane reads 16-byte vectors of its rows, UNROLL of them in
+// flight per row.  The last partial vector of a row (N not a multiple of the vector) is
+// read element by element.  Needs A and x 16-byte aligned and lda a whole number of vectors.
+// ---------------------------------------------------------------------------------------
+constexpr int GEMV_PANEL_BYTES = 32768;
+
+template <typename T>
+__global__ __launch_bounds__(256) void gemv_vec_kernel(const char* A, int64_t lda, const char* x, float* y, int M, int N,
+                                                       float alpha, float beta) {
+  constexpr int ES = ElemSize<T>::value, EPC = 16 / ES, PANEL = GEMV_PANEL_BYTES / ES, UNROLL = 4;
+  __shared__ __attribute__((aligned(16))) char xs[GEMV_PANEL_BYTES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row0 = blockIdx.x * 8 + wave * 2;
+  const bool ok0 = row0 < M, ok1 = row0 + 1 < M;
+  const char* a0 = A + (int64_t)(ok0 ? row0 : 0) * lda * ES;
+  const char* a1 = A + (int64_t)(ok1 ? row0 + 1 : 0) * lda * ES;
+  float acc0 = 0.f, acc1 = 0.f;
+  for (int p0 = 0; p0 < N; p0 += PANEL) {
+    const int pn = min(PANEL, N - p0);                 // elements of x in this panel
+    const int full = pn / EPC;                         // whole vectors
+    __syncthreads();                                   // the previous panel has been consumed
+    for (int c = tid; c < (pn + EPC - 1) / EPC; c += 256) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (c < full) {
+        v = *(const u32x4*)(x + ((int64_t)p0 + (int64_t)c * EPC) * ES);
+      } else {                                         // ragged end of x: element by element, zero beyond N
+        for (int e = 0; e < pn - full * EPC; ++e) {
+          if constexpr (ES == 4) v[e] = ((const uint32_t*)x)[p0 + c * EPC + e];
+          else v[e >> 1] |= (uint32_t)((const uint16_t*)x)[p0 + c * EPC + e] << ((e & 1) * 16);
+        }
+      }
+      *(u32x4*)(xs + c * 16) = v;
+    }
+    __syncthreads();
+    int c = lane;
+    for (; c + (UNROLL - 1) * 64 < full; c += UNROLL * 64) {
+      u32x4 va[UNROLL], vb[UNROLL];
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) {
+        const int64_t off = ((int64_t)p0 + (int64_t)(c + u * 64) * EPC) * ES;
+        va[u] = *(const u32x4*)(a0 + off);
+        vb[u] = *(const u32x4*)(a1 + off);
+      }
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) {
+        float fx[EPC], fa[EPC], fb[EPC];
+        unpack_chunk<T>(*(const u32x4*)(xs + (c + u * 64) * 16), fx);
+        unpack_chunk<T>(va[u], fa);
+        unpack_chunk<T>(vb[u], fb);
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+          acc0 = fmaf(fa[e], fx[e], acc0);
+          acc1 = fmaf(fb[e], fx[e], acc1);
+        }
+      }
+    }
+    for (; c < full; c += 64) {
+      const int64_t off = ((int64_t)p0 + (int64_t)c * EPC) * ES;
+      float fx[EPC], fa[EPC], fb[EPC];
+      unpack_chunk<T>(*(const u32x4*)(xs + c * 16), fx);
+      unpack_chunk<T>(*(const u32x4*)(a0 + off), fa);
+      unpack_chunk<T>(*(const u32x4*)(a1 + off), fb);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+        acc0 = fmaf(fa[e], fx[e], acc0);
+        acc1 = fmaf(fb[e], fx[e], acc1);
+      }
+    }
+    // ragged end of the rows: lane e takes element e of the partial vector
+    const int rem = pn - full * EPC;
+    if (lane < rem) {
+      const int64_t i = (int64_t)p0 + (int64_t)full * EPC + lane;
+      const float xv = to_float<T>(xs, full * EPC + lane);
+      acc0 = fmaf(to_float<T>(a0, i), xv, acc0);
+      acc1 = fmaf(to_float<T>(a1, i), xv, acc1);
+    }
+  }
+  acc0 = wave_sum(acc0);
+  acc1 = wave_sum(acc1);
+  if (lane == 0) {
+    if (ok0) y[row0] = alpha * acc0 + (beta != 0.f ? beta * y[row0] : 0.f);
+    if (ok1) y[row0 + 1] = alpha * acc1 + (beta != 0.f ? beta * y[row0 + 1] : 0.f);
+  }
+}
+
+// any alignment: one wave per row, element loads
+template <typename T>
+__global__ __launch_bounds__(256) void gemv_scalar_kernel(const char* A, int64_t lda, const char* x, float* y, int M, int N,
+                                                          float alpha, float beta) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;                                // whole waves leave together; no barrier follows
+  float acc = 0.f;
+  for (int n = lane; n < N; n += 64) acc = fmaf(to_float<T>(A, (int64_t)row * lda + n), to_float<T>(x, n), acc);
+  acc = wave_sum(acc);
+  if (lane == 0) y[row] = alpha * acc + (beta != 0.f ? beta * y[row] : 0.f);
+}
+
+// ---------------------------------------------------------------------------------------
+// AvgPooling2d, O[plane][p][q] = (1/F^2) sum_{i,j<F} I[plane][S p + i][S q + j].  One thread
+// per output; consecutive threads take consecutive q, so a wave reads contiguous runs of
+// every input row it touches.  The window is summed in fp32 and divided once by F*F.
+// ---------------------------------------------------------------------------------------
+template <typename T, typename OutT>
+__global__ __launch_bounds__(256) void avgpool_kernel(const void* in, void* out, int64_t total, int H, int W, int P, int Q, int F,
+                                                      int S) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int64_t t = idx / Q;
+  const int q = (int)(idx - t * Q);
+  const int64_t plane = t / P;
+  const int p = (int)(t - plane * P);
+  const int64_t base = (plane * H + (int64_t)S * p) * W + (int64_t)S * q;
+  float acc = 0.f;
+  for (int i = 0; i < F; ++i)
+    for (int j = 0; j < F; ++j) acc += to_float<T>(in, base + (int64_t)i * W + j);
+  store_out<OutT>(out, idx, acc / (float)(F * F));
+}
+
+template <typename T>
+hipError_t launch_gemv(const void* A, int64_t lda, const void* x, float* y, int64_t M, int64_t N, float alpha, float beta, hipStream_t st) {
+  constexpr int ES = ElemSize<T>::value, EPC = 16 / ES;
+  const bool vec = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(x)) & 15u) == 0 && lda % EPC == 0;
+  if (vec)
+    hipLaunchKernelGGL(gemv_vec_kernel<T>, dim3((unsigned)((M + 7) / 8)), dim3(256), 0, st, (const char*)A, lda, (const char*)x, y,
+                       (int)M, (int)N, alpha, beta);
+  else
+    hipLaunchKernelGGL(gemv_scalar_kernel<T>, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, (const char*)A, lda, (const char*)x, y,
+                       (int)M, (int)N, alpha, beta);
+  return hipGetLastError();
+}
+
+template <typename T, typename OutT>
+hipError_t launch_pool(const void* in, void* out, int64_t planes, int64_t h, int64_t w, int64_t f, int64_t s, hipStream_t st) {
+  const int64_t P = (h - f) / s + 1, Q = (w - f) / s + 1, total = planes * P * Q;
+  hipLaunchKernelGGL((avgpool_kernel<T, OutT>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, in, out, total, (int)h, (int)w,
+                     (int)P, (int)Q, (int)f, (int)s);
+  return hipGetLastError();
+}
+
+}  // namespace gensor
+
+using namespace gensor;
+
+extern "C" gensor_status gensor_gemv(gensor_dtype in_dtype, int64_t M, int64_t N, float alpha, const void* A, int64_t lda,
+                                     const void* x, float beta, float* y, void* hip_stream) {
+  if (!A || !x || !y || M <= 0 || N <= 0 || lda < N) return GENSOR_ERR_INVALID_ARG;
+  if (M > INT32_MAX - 8 || N > INT32_MAX - GEMV_PANEL_BYTES) return GENSOR_ERR_UNSUPPORTED;
+  hipError_t e;
+  switch (in_dtype) {
+    case GENSOR_F32: e = launch_gemv<f32_t>(A, lda, x, y, M, N, alpha, beta, (hipStream_t)hip_stream); break;
+    case GENSOR_F16: e = launch_gemv<f16_t>(A, lda, x, y, M, N, alpha, beta, (hipStream_t)hip_stream); break;
+    case GENSOR_BF16: e = launch_gemv<bf16_t>(A, lda, x, y, M, N, alpha, beta, (hipStream_t)hip_stream); break;
+    default: return GENSOR_ERR_INVALID_ARG;
+  }
+  return e == hipSuccess ? GENSOR_OK : GENSOR_ERR_DEVICE;
+}
+
+extern "C" gensor_status gensor_avgpool2d(gensor_dtype in_dtype, gensor_dtype out_dtype, int64_t n, int64_t c, int64_t h, int64_t w,
+                                          int64_t f, int64_t stride, const void* input, void* output, void* hip_stream) {
+  if (!input || !output || n <= 0 || c <= 0 || h <= 0 || w <= 0 || f <= 0 || stride <= 0 || f > h || f > w) return GENSOR_ERR_INVALID_ARG;
+  if (in_dtype != GENSOR_F32 && in_dtype != GENSOR_F16 && in_dtype != GENSOR_BF16) return GENSOR_ERR_INVALID_ARG;
+  if (out_dtype != GENSOR_F32 && out_dtype != in_dtype) return GENSOR_ERR_UNSUPPORTED;
+  const int64_t P = (h - f) / stride + 1, Q = (w - f) / stride + 1;
+  if (h > INT32_MAX || w > INT32_MAX || f > 4096 || (n * c * P * Q + 255) / 256 > INT32_MAX) return GENSOR_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int64_t planes = n * c;
+  hipError_t e;
+  if (in_dtype == GENSOR_F32) e = launch_pool<f32_t, f32_t>(input, output, planes, h, w, f, stride, st);
+  else if (in_dtype == GENSOR_F16)
+    e = out_dtype == GENSOR_F32 ? launch_pool<f16_t, f32_t>(input, output, planes, h, w, f, stride, st)
+                                : launch_pool<f16_t, f16_t>(input, output, planes, h, w, f, stride, st);
+  else
+    e = out_dtype == GENSOR_F32 ? launch_pool<bf16_t, f32_t>(input, output, planes, h, w, f, stride, st)
+                                : launch_pool<bf16_t, bf16_t>(input, output, planes, h, w, f, stride, st);
+  return e == hipSuccess ? GENSOR_OK : GENSOR_ERR_DEVICE;
+}

@@ -214,6 +214,32 @@ def unbalanced_gemm(index: int, dtype: str = "f16") -> GemmWorkload:
                          lambda s: uniform_pm1(_seed(6 + index, 1), s, dtype))
 
 
+GEMV_SHAPES = [(16384, 16384), (16384, 8192), (16384, 1000)]                      # V1-V3: [M, N]
+POOL_SHAPES = [(16, 48, 48, 48, 2, 2), (128, 168, 83, 83, 2, 2), (128, 617, 21, 21, 3, 2)]   # P1-P3: n, c, h, w, F, S
+PAPER_CONVS = [(128, 256, 30, 30, 256, 3, 2), (128, 128, 28, 28, 128, 3, 1), (128, 128, 58, 58, 128, 3, 2)]   # C1-C3: n, c, h, w, k, r, S
+
+
+def gemv_workload(index: int, dtype: str = "f16"):
+    """GEMV shape V1-V3 of the paper's operator table: (A [M][N], x [N]), uniform [-1, 1)."""
+    M, N = GEMV_SHAPES[index]
+    return uniform_pm1(_seed(11 + index, 0), (M, N), dtype), uniform_pm1(_seed(11 + index, 1), (N,), dtype)
+
+
+def pool_workload(index: int, dtype: str = "f16"):
+    """AvgPooling2d shape P1-P3 of the operator table: (input NCHW, F, S), N(0, 1) values."""
+    n, c, h, w, f, s = POOL_SHAPES[index]
+    return normal(_seed(14 + index, 0), (n, c, h, w), dtype, 1.0), f, s
+
+
+def paper_conv(index: int, dtype: str = "f16") -> "ConvWorkload":
+    """Conv2d shape C1-C3 of the operator table (inputs printed already padded: no padding here)."""
+    n, c, h, w, k, r, stride = PAPER_CONVS[index]
+    cw = ConvWorkload(f"conv_C{index + 1}_{dtype}", dtype, n, c, h, w, k, r, r, stride, 0)
+    cw.I = normal(_seed(17 + index, 0), (n, c, h, w), dtype, 1.0)
+    cw.W = normal(_seed(17 + index, 1), (k, c, r, r), dtype, math.sqrt(2.0 / (c * r * r)))
+    return cw
+
+
 def all_configs() -> Dict[str, object]:
     return {
         "cfg1": config1_gemm_f32(),

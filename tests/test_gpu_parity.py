@@ -398,3 +398,102 @@ def test_mfma_probe_counts_its_flops(gs, dtype):
     assert torch.all(sink == 2048.0 * 10).item()
     with pytest.raises(gs.GensorError):
         gs.mfma_probe("f32", gs.to_device(np.ones(64 * 1024, dtype=np.float32), "f32"), sink, 10)
+
+
+# ------------------------------------------------------------------ GEMV and AvgPooling2d
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("M,N", [(1, 1), (7, 5), (8, 64), (37, 1000), (130, 520), (9, 20011), (16, 32768 + 8)])
+def test_gemv_bit_exact_on_integers(gs, dtype, M, N):
+    """Several workgroups, rows that are no multiple of 8, ragged vector tails, x longer than one LDS panel."""
+    import torch
+    A = inputs.small_ints(41, (M, N), dtype, -2, 2)
+    x = inputs.small_ints(42, (N,), dtype, -2, 2)
+    y0 = inputs.small_ints(43, (M,), "f32", -4, 4)
+    dA, dx = gs.to_device(A, dtype), gs.to_device(x, dtype)
+    y = torch.full((M,), float("nan"), dtype=torch.float32, device="cuda")          # beta = 0 must not read it
+    gs.gemv(dtype, dA, dx, y)
+    torch.cuda.synchronize()
+    assert np.array_equal(gs.to_host_f64(y), ops.gemv(A, x, dtype))
+    y = gs.to_device(y0, "f32")
+    gs.gemv(dtype, dA, dx, y, alpha=2.0, beta=-3.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(gs.to_host_f64(y), ops.gemv(A, x, dtype, alpha=2.0, beta=-3.0, y0=y0))
+
+
+def test_gemv_unaligned_operands_and_errors(gs):
+    """A view with an odd leading dimension and an offset start takes the element-load kernel."""
+    import torch
+    A = inputs.small_ints(44, (33, 77), "f16", -2, 2)
+    x = inputs.small_ints(45, (77,), "f16", -2, 2)
+    dA, dx = gs.to_device(A, "f16"), gs.to_device(np.concatenate([x[:1], x]), "f16")[1:]
+    sub = dA[:, 3:70]                                        # lda = 77, start 6 bytes into a row
+    y = torch.zeros(33, dtype=torch.float32, device="cuda")
+    gs.gemv("f16", sub, dx[3:70], y)
+    torch.cuda.synchronize()
+    assert np.array_equal(gs.to_host_f64(y), ops.gemv(np.ascontiguousarray(A[:, 3:70]), x[3:70], "f16"))
+    with pytest.raises(gs.GensorError) as e:
+        gs.gemv("f16", dA, dx, y, lda=10)                    # lda < N
+    assert e.value.status == 1
+
+
+@pytest.mark.parametrize("index", range(3))
+def test_gemv_paper_shapes_full_size(gs, index):
+    import torch
+    A, x = inputs.gemv_workload(index)
+    y = torch.full((A.shape[0],), float("nan"), dtype=torch.float32, device="cuda")
+    gs.gemv("f16", gs.to_device(A, "f16"), gs.to_device(x, "f16"), y)
+    torch.cuda.synchronize()
+    rows = inputs.sample_indices(46, (A.shape[0],), 400)[:, 0]
+    want = ops.gemv(np.ascontiguousarray(A[rows]), x, "f16")
+    got = gs.to_host_f64(y)
+    err = ops.rel_frobenius(got[rows], want)
+    print("gemv", A.shape, "rel frobenius on sampled rows", err)
+    assert np.isfinite(got).all() and err <= 1e-5
+
+
+@pytest.mark.parametrize("dtype,out_dtype", [("f32", "f32"), ("f16", "f32"), ("bf16", "f32"), ("f16", "f16")])
+@pytest.mark.parametrize("n,c,h,w,f,stride", [(2, 3, 8, 10, 2, 2), (1, 5, 9, 7, 3, 2), (3, 2, 7, 9, 2, 2), (2, 2, 6, 6, 3, 1),
+                                              (1, 1, 5, 300, 4, 4), (2, 4, 17, 33, 1, 1)])
+def test_avgpool_small_cases(gs, dtype, out_dtype, n, c, h, w, f, stride):
+    """Window sums of small integers are exact in fp32; dividing by a power of two keeps them exact, so F in
+    {1, 2, 4} must agree bit for bit; F = 3 divides by 9 and is held to one fp32 rounding."""
+    import torch
+    I = inputs.small_ints(47, (n, c, h, w), dtype, -8, 8)
+    want = ops.avgpool2d(I, dtype, f, stride)
+    O = gs.empty_device(want.shape, out_dtype)
+    O.fill_(float("nan"))
+    gs.avgpool2d(dtype, gs.to_device(I, dtype), O, f, stride, out_dtype)
+    torch.cuda.synchronize()
+    got = gs.to_host_f64(O)
+    if f in (1, 2, 4) and out_dtype == "f32":
+        assert np.array_equal(got, want)
+    else:
+        tol = 2.0 ** -24 if out_dtype == "f32" else 2.0 ** -11
+        assert np.abs(got - want).max() <= tol * max(1.0, np.abs(want).max())
+
+
+@pytest.mark.parametrize("index", range(3))
+def test_avgpool_paper_shapes_full_size(gs, index):
+    import torch
+    I, f, stride = inputs.pool_workload(index)
+    shape = ops.pool_out_shape(*I.shape, f, stride)
+    O = gs.empty_device(shape)
+    O.fill_(float("nan"))
+    gs.avgpool2d("f16", gs.to_device(I, "f16"), O, f, stride)
+    torch.cuda.synchronize()
+    co = inputs.sample_indices(48, shape, 3000)
+    want = ops.avgpool2d_at(I, "f16", co, f, stride)
+    idx = torch.from_numpy(co).cuda()
+    got = O[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].double().cpu().numpy()
+    err = ops.rel_frobenius(got, want)
+    print("avgpool", I.shape, f, stride, "rel frobenius on samples", err)
+    assert bool(torch.isfinite(O).all()) and err <= 1e-6
+
+
+@pytest.mark.parametrize("index", range(3))
+def test_paper_conv_shapes_full_size(gs, index):
+    """Conv2d shapes C1-C3 of the operator table with the constructed schedule."""
+    w, s, got, want, finite = _full_size_case(gs, inputs.paper_conv(index))
+    err = ops.rel_frobenius(got, want)
+    print(w.name, "kernel", s.kernel_id, "rel frobenius on samples", err)
+    assert finite and err <= 1e-5
