@@ -132,13 +132,78 @@ __global__ __launch_bounds__(256) void gemv_scalar_kernel(const char* A, int64_t
 }
 
 // ---------------------------------------------------------------------------------------
-// AvgPooling2d, O[plane][p][q] = (1/F^2) sum_{i,j<F} I[plane][S p + i][S q + j].  One thread
-// per output; consecutive threads take consecutive q, so a wave reads contiguous runs of
-// every input row it touches.  The window is summed in fp32 and divided once by F*F.
+// AvgPooling2d, O[plane][p][q] = (1/F^2) sum_{i,j<F} I[plane][S p + i][S q + j].  The window
+// is summed in fp32 and divided once by F*F.
+//
+// avgpool_lds_kernel: the input a workgroup needs is one contiguous span of the NCHW tensor
+// (whole planes, or the rows under a run of output rows of one plane).  It is brought into
+// LDS with aligned 16-byte vector loads (2-byte loads per window element would make the load
+// pipeline, not HBM, the limit), and the windows are then read from LDS.
+// avgpool_direct_kernel: one thread per output straight from global memory, for inputs that
+// are not 16-byte aligned or whose rows do not fit the LDS span.
 // ---------------------------------------------------------------------------------------
+constexpr int POOL_SPAN_BYTES = 32768;
+
 template <typename T, typename OutT>
-__global__ __launch_bounds__(256) void avgpool_kernel(const void* in, void* out, int64_t total, int H, int W, int P, int Q, int F,
-                                                      int S) {
+__global__ __launch_bounds__(256) void avgpool_lds_kernel(const char* in, void* out, int64_t in_bytes, int planes, int H, int W, int P,
+                                                          int Q, int F, int S, int planes_per_wg, int rows_per_wg, int chunks_per_plane) {
+  constexpr int ES = ElemSize<T>::value;
+  __shared__ __attribute__((aligned(16))) char span[POOL_SPAN_BYTES + 16];
+  const int tid = threadIdx.x;
+  const int group = blockIdx.x / chunks_per_plane, chunk = blockIdx.x - group * chunks_per_plane;
+  const int plane0 = group * planes_per_wg;
+  const int nplanes = min(planes_per_wg, planes - plane0);
+  const int p0 = chunk * rows_per_wg;
+  const int nrows = min(rows_per_wg, P - p0);
+  // span of input elements [e0, e0 + len)
+  const int64_t e0 = ((int64_t)plane0 * H + (int64_t)S * p0) * W;
+  const int len = chunks_per_plane == 1 ? nplanes * H * W : ((nrows - 1) * S + F) * W;
+  const int64_t b0 = e0 * ES, a0 = b0 & ~(int64_t)15;
+  const int skew = (int)(b0 - a0);                            // bytes before the first element in LDS
+  const int nvec = (skew + len * ES + 15) / 16;
+  for (int v = tid; v < nvec; v += 256) {
+    const int64_t addr = a0 + (int64_t)v * 16;
+    u32x4 d = {0u, 0u, 0u, 0u};
+    if (addr + 16 <= in_bytes) {
+      d = *(const u32x4*)(in + addr);
+    } else {                                                  // last vector of the tensor: element by element
+      for (int e = 0; e < 16 / ES; ++e) {
+        if (addr + (e + 1) * ES <= in_bytes) {
+          if constexpr (ES == 4) d[e] = *(const uint32_t*)(in + addr + e * 4);
+          else d[e >> 1] |= (uint32_t)*(const uint16_t*)(in + addr + e * 2) << ((e & 1) * 16);
+        }
+      }
+    }
+    *(u32x4*)(span + v * 16) = d;
+  }
+  __syncthreads();
+  const int per_plane = nrows * Q;
+  const int total = nplanes * per_plane;
+  const float count = (float)(F * F);
+  // thread t takes outputs t, t + 256, ...; (plane, row, column) advance incrementally
+  int g = tid / per_plane, pr, q;
+  {
+    const int r = tid - g * per_plane;
+    pr = r / Q;
+    q = r - pr * Q;
+  }
+  const int dq = 256 % Q, dp = 256 / Q;
+  for (int t = tid; t < total; t += 256) {
+    const int base = (g * H + S * pr) * W + S * q;            // element offset inside the span
+    float acc = 0.f;
+    for (int i = 0; i < F; ++i)
+      for (int j = 0; j < F; ++j) acc += to_float<T>(span + skew, base + i * W + j);
+    store_out<OutT>(out, ((int64_t)(plane0 + g) * P + p0 + pr) * Q + q, acc / count);
+    q += dq;
+    pr += dp;
+    if (q >= Q) { q -= Q; ++pr; }
+    while (pr >= nrows) { pr -= nrows; ++g; }
+  }
+}
+
+template <typename T, typename OutT>
+__global__ __launch_bounds__(256) void avgpool_direct_kernel(const void* in, void* out, int64_t total, int H, int W, int P, int Q, int F,
+                                                             int S) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
   const int64_t t = idx / Q;
@@ -167,9 +232,33 @@ hipError_t launch_gemv(const void* A, int64_t lda, const void* x, float* y, int6
 
 template <typename T, typename OutT>
 hipError_t launch_pool(const void* in, void* out, int64_t planes, int64_t h, int64_t w, int64_t f, int64_t s, hipStream_t st) {
-  const int64_t P = (h - f) / s + 1, Q = (w - f) / s + 1, total = planes * P * Q;
-  hipLaunchKernelGGL((avgpool_kernel<T, OutT>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, in, out, total, (int)h, (int)w,
-                     (int)P, (int)Q, (int)f, (int)s);
+  constexpr int ES = ElemSize<T>::value;
+  const int64_t P = (h - f) / s + 1, Q = (w - f) / s + 1;
+  const int64_t plane_bytes = h * w * ES, row_bytes = w * ES;
+  const bool aligned = (reinterpret_cast<uintptr_t>(in) & 15u) == 0;
+  int64_t G = 0, R = 0, cpp = 0;
+  if (aligned && plane_bytes <= POOL_SPAN_BYTES) {             // whole planes per workgroup
+    G = POOL_SPAN_BYTES / plane_bytes;
+    const int64_t cap = (8192 + P * Q - 1) / (P * Q);          // keep a workgroup to a few thousand outputs
+    if (G > cap) G = cap;
+    if (G > planes) G = planes;
+    R = P;
+    cpp = 1;
+  } else if (aligned && f * row_bytes <= POOL_SPAN_BYTES) {    // runs of output rows of one plane
+    G = 1;
+    R = (POOL_SPAN_BYTES / row_bytes - f) / s + 1;
+    if (R > P) R = P;
+    cpp = (P + R - 1) / R;
+  }
+  const int64_t groups = G ? (planes + G - 1) / G * cpp : 0;
+  if (G && groups <= INT32_MAX && planes <= INT32_MAX) {
+    hipLaunchKernelGGL((avgpool_lds_kernel<T, OutT>), dim3((unsigned)groups), dim3(256), 0, st, (const char*)in, out,
+                       planes * plane_bytes, (int)planes, (int)h, (int)w, (int)P, (int)Q, (int)f, (int)s, (int)G, (int)R, (int)cpp);
+  } else {
+    const int64_t total = planes * P * Q;
+    hipLaunchKernelGGL((avgpool_direct_kernel<T, OutT>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, in, out, total, (int)h,
+                       (int)w, (int)P, (int)Q, (int)f, (int)s);
+  }
   return hipGetLastError();
 }
 

@@ -453,7 +453,10 @@ def test_gemv_paper_shapes_full_size(gs, index):
 
 @pytest.mark.parametrize("dtype,out_dtype", [("f32", "f32"), ("f16", "f32"), ("bf16", "f32"), ("f16", "f16")])
 @pytest.mark.parametrize("n,c,h,w,f,stride", [(2, 3, 8, 10, 2, 2), (1, 5, 9, 7, 3, 2), (3, 2, 7, 9, 2, 2), (2, 2, 6, 6, 3, 1),
-                                              (1, 1, 5, 300, 4, 4), (2, 4, 17, 33, 1, 1)])
+                                              (1, 1, 5, 300, 4, 4), (2, 4, 17, 33, 1, 1),
+                                              (3, 37, 21, 21, 3, 2),        # many small planes per workgroup, ragged last group
+                                              (1, 2, 150, 131, 2, 2),       # a plane larger than the LDS span: runs of output rows
+                                              (1, 1, 3, 20000, 2, 1)])      # rows too long for the span: direct kernel
 def test_avgpool_small_cases(gs, dtype, out_dtype, n, c, h, w, f, stride):
     """Window sums of small integers are exact in fp32; dividing by a power of two keeps them exact, so F in
     {1, 2, 4} must agree bit for bit; F = 3 divides by 9 and is held to one fp32 rounding."""
@@ -465,6 +468,12 @@ def test_avgpool_small_cases(gs, dtype, out_dtype, n, c, h, w, f, stride):
     gs.avgpool2d(dtype, gs.to_device(I, dtype), O, f, stride, out_dtype)
     torch.cuda.synchronize()
     got = gs.to_host_f64(O)
+    if out_dtype == "f32" and dtype == "f16":                # an input that does not start on a 16-byte boundary
+        shifted = gs.to_device(np.concatenate([I.reshape(-1)[:1], I.reshape(-1)]), dtype)[1:].view(n, c, h, w)
+        O2 = gs.empty_device(want.shape, out_dtype)
+        gs.avgpool2d(dtype, shifted, O2, f, stride, out_dtype)
+        torch.cuda.synchronize()
+        assert np.array_equal(gs.to_host_f64(O2), got)
     if f in (1, 2, 4) and out_dtype == "f32":
         assert np.array_equal(got, want)
     else:
