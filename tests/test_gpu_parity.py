@@ -506,3 +506,27 @@ def test_paper_conv_shapes_full_size(gs, index):
     err = ops.rel_frobenius(got, want)
     print(w.name, "kernel", s.kernel_id, "rel frobenius on samples", err)
     assert finite and err <= 1e-5
+
+
+def test_shape_changes_reconstruct_within_a_latency_budget(gs):
+    """Dynamic shapes: a call without a schedule constructs one for a shape it has not seen (a few
+    milliseconds on the host) and reuses it afterwards; results stay exact across the shape changes."""
+    import time
+    import torch
+    first, again = [], []
+    for i, (M, N, K) in enumerate([(96 + 32 * j, 200 + 8 * j, 64 * (1 + j % 3)) for j in range(12)]):
+        A = inputs.small_ints(60 + i, (M, K), "f16", -2, 2)
+        B = inputs.small_ints(80 + i, (K, N), "f16", -2, 2)
+        p = gs.gemm_problem("f16", M, N, K, 0, 0)
+        dA, dB = gs.to_device(A, "f16"), gs.to_device(B, "f16")
+        dC = gs.empty_device((M, N))
+        torch.cuda.synchronize()
+        for bucket in (first, again):
+            t0 = time.perf_counter()
+            gs.gemm(p, dA, dB, dC, 1.0, 0.0, None)
+            torch.cuda.synchronize()
+            bucket.append(time.perf_counter() - t0)
+        assert np.array_equal(gs.to_host_f64(dC), ops.gemm(A, B, "f16"))
+    print("first call per new shape: max %.1f ms, repeated: max %.2f ms" % (1e3 * max(first[1:]), 1e3 * max(again)))
+    assert max(first[1:]) < 0.25            # construction plus launch (the very first call also loads the code object)
+    assert max(again) < max(0.05, max(first[1:]))
