@@ -47,7 +47,7 @@ COLD_BYTES = 640 << 20     # operand sets rotated through in the cold-cache timi
 class Case:
     """One workload resident on the device with its constructed schedule."""
 
-    def __init__(self, gs, inputs, w):
+    def __init__(self, gs, inputs, w, opts=None):
         import torch
         self.gs, self.w = gs, w
         self.is_gemm = isinstance(w, inputs.GemmWorkload)
@@ -60,7 +60,7 @@ class Case:
             self.a, self.b = gs.to_device(w.I, w.dtype), gs.to_device(w.W, w.dtype)
             self.out = gs.empty_device((w.n, w.k, w.p, w.q))
         t0 = time.perf_counter()
-        self.sched = gs.construct(self.p, seed=0)
+        self.sched = gs.construct(self.p, seed=0, opts=opts)
         self.construct_s = time.perf_counter() - t0
         self.ws = None if self.is_gemm else gs.conv_workspace(self.p, self.sched)
         self.sets = [(self.a, self.b, self.out)]
@@ -236,6 +236,37 @@ def operator_table_rows(gs, inputs):
     return rows
 
 
+def ablation(gs, inputs):
+    """Variants of the walk on this hardware (the design of the paper's ablation, Table VI): each
+    constructs a schedule for three shapes; the schedule is then timed."""
+    import torch
+    variants = [("full", None),
+                ("no_vthread", gs.ConstructOpts(0, 0, 0, 0, 0, 1)),
+                ("printed_keep_probability", gs.ConstructOpts(0, 0, 0, 1, 0, 0)),
+                ("footprint_ratio_inverted", gs.ConstructOpts(0, 0, 0, 0, 1, 0)),
+                ("one_walk", gs.ConstructOpts(0, 0, 1, 0, 0, 0)),
+                ("T0_1_as_literal", gs.ConstructOpts(1.0, 2.0 ** -100, 0, 0, 0, 0))]
+    out = []
+    cfgs = inputs.all_configs()
+    for name in ("cfg2", "cfg3_up", "cfg5_3x3"):
+        wl = cfgs[name]
+        row = {"workload": wl.name}
+        for vname, opts in variants:
+            try:
+                c = Case(gs, inputs, wl, opts)
+            except gs.GensorError as e:
+                row[vname] = {"error": str(e)}
+                continue
+            m = c.time_median_ms(30, 100, batches=3)
+            row[vname] = {"kernel_id": c.sched.kernel_id, "us": m * 1e3, "tflops": wl.flops / (m * 1e-3) / 1e12,
+                          "predicted_us": c.sched.predicted_us, "states_scored": c.sched.states_scored,
+                          "construct_s": c.construct_s}
+            del c
+            torch.cuda.empty_cache()
+        out.append(row)
+    return out
+
+
 def cpu_baseline(w):
     """The oracle as it stands on a bounded slice (leading rows of A) of the headline GEMM."""
     from oracle import ops
@@ -355,6 +386,7 @@ def main():
             torch.cuda.empty_cache()
         line["unbalanced_gemms"] = nxt
         line["operator_table"] = operator_table_rows(gs, inputs)
+        line["ablation"] = ablation(gs, inputs)
         line["cpu_baseline"] = cpu_baseline(w)
         line["paper_context"] = ("paper (RTX 4090, precision not stated): GEMM 45.2 TFLOP/s, Conv2d C1 34.54 TFLOP/s, "
                                  "construction 'a few seconds' (Table VI, Fig. 8 caption)")
