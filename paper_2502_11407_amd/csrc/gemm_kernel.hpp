@@ -29,6 +29,8 @@
 // is consumed differs from memory order, identically for both operands.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 #include <stdint.h>
 
 namespace gensor {
@@ -565,11 +567,15 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   wait_deposits();
   __syncthreads();
   if constexpr (PIPE) {
-    read_frags(0, 0, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-      const bool more = kt + 1 < nk;
+    // Whether a further k tile follows is a compile-time property of the loop body: the last k
+    // tile is peeled.  With a run-time test the two paths would meet in front of the last k
+    // step's MFMAs, where the compiler must then wait for the fragment reads issued after the
+    // barrier (they are outstanding on one path only), which stalls every wave of the workgroup
+    // at the same moment once per k tile.
+    auto k_tile = [&](int kt, auto more_tag) {
+      constexpr bool more = decltype(more_tag)::value;
       const int cur = kt & 1, nxt = cur ^ 1;
-      if (more) {
+      if constexpr (more) {
         fetch_a((kt + 1) * BK, nxt);
         fetch_b((kt + 1) * BK, nxt);
       }
@@ -577,7 +583,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       for (int ks = 0; ks < C::KSTEPS; ++ks) {
         if (ks + 1 < C::KSTEPS) {
           read_frags(cur, ks + 1, (ks + 1) & 1);
-        } else if (more) {
+        } else if constexpr (more) {
           commit(nxt);
           wait_deposits();
           __syncthreads();
@@ -586,7 +592,10 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         mma(ks & 1);
         interleave();
       }
-    }
+    };
+    read_frags(0, 0, 0);
+    for (int kt = 0; kt + 1 < nk; ++kt) k_tile(kt, std::true_type{});
+    k_tile(nk - 1, std::false_type{});
   } else {
     for (int kt = 0; kt < nk; ++kt) {
       const bool more = kt + 1 < nk;
