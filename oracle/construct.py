@@ -473,8 +473,13 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     if direct and view.bsrc == 0:          # measured: direct staging pays for k-contiguous operands only
         overlap += 0.05
     # every k tile boundary (barrier, refill of the fragment pipeline) exposes a share of the memory latency
+    # (a ring of three and more stages keeps more tiles in flight; measured to pay for k-contiguous operands)
     t_ktile = 0.25 * hw.latency_ns[0] * 1e-3
-    t_main = max(t_mfma, t_lds, t_feed) / overlap + math.ceil(view.K / bk) * t_ktile
+    nk = float(math.ceil(view.K / bk))
+    t_sync = nk * t_ktile
+    if stages > 2 and view.bsrc == 0:
+        t_sync = t_sync / (stages - 1)
+    t_main = max(t_mfma, t_lds, t_feed) / overlap + t_sync
     hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units
     t_epi = bm * bn * eo / (0.8 * hbm_bw_cu)
     t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3

@@ -356,8 +356,12 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   if (t_lds > t_main) t_main = t_lds;
   if (t_feed > t_main) t_main = t_feed;
   // every k tile boundary (barrier, refill of the fragment pipeline) exposes a share of the memory latency
+  // (a ring of three and more stages keeps more tiles in flight; measured to pay for k-contiguous operands)
   const double t_ktile = 0.25 * hw.latency_ns[0] * 1e-3;
-  t_main = t_main / overlap + std::ceil((double)v.K / bk) * t_ktile;
+  const double nk = std::ceil((double)v.K / bk);
+  double t_sync = nk * t_ktile;
+  if (stages > 2 && v.bsrc == B_KC) t_sync = t_sync / (stages - 1);
+  t_main = t_main / overlap + t_sync;
   const double hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units;
   const double t_epi = bm * bn * eo / (0.8 * hbm_bw_cu);
   const double t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3;

@@ -7,7 +7,8 @@
 //   WM,WN      T_1  wavefront tile, fp32 accumulators in registers
 //   MB         MFMA block edge (32: 32x32 blocks, 16: 16x16 blocks); fixes the MFMA k depth
 //   VM,VN      virtual-thread split: the wave tile is V strided pieces of T_0 = T_1/V rows
-//   STAGES     LDS buffers (1: single buffer, 2: double buffer)
+//   STAGES     LDS buffers (1: single buffer, 2: double buffer, 3 and more: a ring that keeps STAGES-1
+//              k tiles in flight; direct staging only)
 //   VEC        global accesses are 16-byte vectors (true) or single elements (false)
 //   DIRECT     K-contiguous operands go global->LDS without passing through registers
 //
@@ -186,6 +187,9 @@ struct Cfg {
   static_assert(!NC_DIRECT || (B_CHUNKS % THREADS == 0), "direct staging deposits whole waves");
   static_assert(BSRC != B_NCS2 || VEC, "the sampled source exists only with vector loads");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS capacity");
+  static_assert(STAGES <= 2 || (DIRECT && VEC && (BSRC == B_KC || BSRC == B_NC) && KSTEPS % 2 == 0),
+                "rings of three and more stages are filled by direct loads");
+  static_assert(STAGES <= 2 || (A_LOADS + B_LOADS) * (STAGES - 2) <= 63, "the load counter holds 63");
 };
 
 __device__ inline int swizzled_chunk(int row, int chunk, int rpp, int cpr) { return chunk ^ ((row / rpp) % cpr); }
@@ -561,12 +565,67 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   // of tile kt, so that the barrier and the LDS latency are covered by matrix work.
   const int nk = (args.K + BK - 1) / BK;
   constexpr bool PIPE = (C::KSTEPS % 2 == 0) && C::STAGES == 2;
-  fetch_a(0, 0);
-  fetch_b(0, 0);
-  commit(0);
-  wait_deposits();
-  __syncthreads();
-  if constexpr (PIPE) {
+  if constexpr (C::STAGES <= 2) {
+    fetch_a(0, 0);
+    fetch_b(0, 0);
+    commit(0);
+    wait_deposits();
+    __syncthreads();
+  }
+  if constexpr (C::STAGES > 2) {
+    // Ring of STAGES buffers: STAGES-1 k tiles are in flight, so a tile has STAGES-1 tile times to
+    // arrive.  Loads complete in issue order, hence "tile kt+1 has landed" is "at most the loads
+    // of the STAGES-2 younger tiles are outstanding"; near the end of k fewer tiles are in flight
+    // and the wait is for all of them.  Three copies of the body (steady state, draining, last
+    // tile) keep those facts compile-time.  The stage refilled at the top of tile kt is the one
+    // read during tile kt-1, which every wave left before the barrier that ended that tile.
+    constexpr int S = C::STAGES;
+    constexpr int LPT = C::A_LOADS + C::B_LOADS;             // loads per thread and tile
+    constexpr int WAIT_STEADY = 0x0F70 | ((LPT * (S - 2)) & 0xF) | (((LPT * (S - 2)) >> 4) << 14);
+    // This wave's LDS reads are complete (its loads in flight are left alone), then the workgroup
+    // barrier: the waits above have made the awaited deposits of every wave visible before it.
+    auto ring_barrier = [&]() {
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+      __builtin_amdgcn_s_barrier();
+    };
+    auto k_tile = [&](int kt, int cur, auto fetch_tag, auto more_tag) {
+      constexpr bool fetch = decltype(fetch_tag)::value, more = decltype(more_tag)::value;
+      const int nxt = cur + 1 == S ? 0 : cur + 1;
+      if constexpr (fetch) {
+        const int dst = cur == 0 ? S - 1 : cur - 1;
+        fetch_a((kt + S - 1) * BK, dst);
+        fetch_b((kt + S - 1) * BK, dst);
+      }
+#pragma unroll
+      for (int ks = 0; ks < C::KSTEPS; ++ks) {
+        if (ks + 1 < C::KSTEPS) {
+          read_frags(cur, ks + 1, (ks + 1) & 1);
+        } else if constexpr (more) {
+          if constexpr (fetch) __builtin_amdgcn_s_waitcnt(WAIT_STEADY);
+          else __builtin_amdgcn_s_waitcnt(0x0F70);
+          ring_barrier();
+          read_frags(nxt, 0, 0);
+        }
+        mma(ks & 1);
+        interleave();
+      }
+      return nxt;
+    };
+#pragma unroll
+    for (int t = 0; t < S - 1; ++t)
+      if (t < nk) {
+        fetch_a(t * BK, t);
+        fetch_b(t * BK, t);
+      }
+    if (nk >= S - 1) __builtin_amdgcn_s_waitcnt(WAIT_STEADY);      // S-1 tiles issued: tile 0 is the oldest
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    ring_barrier();
+    read_frags(0, 0, 0);
+    int cur = 0, kt = 0;
+    for (; kt + S - 1 < nk; ++kt) cur = k_tile(kt, cur, std::true_type{}, std::true_type{});
+    for (; kt + 1 < nk; ++kt) cur = k_tile(kt, cur, std::false_type{}, std::true_type{});
+    k_tile(kt, cur, std::false_type{}, std::false_type{});
+  } else if constexpr (PIPE) {
     // Whether a further k tile follows is a compile-time property of the loop body: the last k
     // tile is peeled.  With a run-time test the two paths would meet in front of the last k
     // step's MFMAs, where the compiler must then wait for the fragment reads issued after the

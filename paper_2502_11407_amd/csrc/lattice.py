@@ -63,6 +63,10 @@ def lattice():
         for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles16:
             if bm * bn >= 128 * 128 and bn >= 128:
                 out.append(_inst(dt, "f32", bm, bn, bk, wm, wn, mb, vm, vn, "NC", direct=1))
+        # a ring of three LDS stages (two k tiles in flight) for the mid-size eight-wave tiles; measured to pay
+        # for k-contiguous operands only
+        for (bm, bn) in ((128, 256), (256, 128)):
+            out.append(_inst(dt, "f32", bm, bn, 64, 64, 64, 32, 1, 1, "KC", stages=3, direct=1))
         # 16-bit output variants
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "KC"))
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "NC"))

@@ -530,3 +530,28 @@ def test_shape_changes_reconstruct_within_a_latency_budget(gs):
     print("first call per new shape: max %.1f ms, repeated: max %.2f ms" % (1e3 * max(first[1:]), 1e3 * max(again)))
     assert max(first[1:]) < 0.25            # construction plus launch (the very first call also loads the code object)
     assert max(again) < max(0.05, max(first[1:]))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("k_tiles", [1, 2, 3, 4, 7])
+def test_ring_staged_instances_across_k_depths(gs, k_tiles):
+    """Instances with three and more LDS stages: fewer k tiles than the ring holds (every fetch is in the
+    prologue), exactly as many, and enough for the steady state, each with ragged m and n, bit-exact on integers."""
+    ran = 0
+    for idx in range(gs.num_instances()):
+        for dt in ("f16", "bf16"):
+            p0 = gs.gemm_problem(dt, 64, 64, 64, 0, 1, 1, "f32")
+            s = gs.instance_schedule(idx, p0)
+            if s is None or s.stages <= 2:
+                continue
+            bm, bn, bk = s.tile[0][0], s.tile[1][0], s.tile[2][0]
+            M, N, K = 2 * bm + 17, bn + 8, k_tiles * bk
+            print(f"instance {idx} {dt} stages {s.stages} tile {bm}x{bn}x{bk} K={K}", flush=True)
+            A = inputs.small_ints(500 + idx, (M, K), dt, -2, 2)
+            B = inputs.small_ints(600 + idx, (N, K), dt, -2, 2)
+            want = ops.gemm(A, B, dt, transB=1)
+            got = run_gemm(gs, dt, M, N, K, 1, s, A, B)
+            assert np.abs(want).max() < 2048
+            assert np.array_equal(got, want), f"instance {idx} K={K}: max abs diff {np.abs(got - want).max()}"
+            ran += 1
+    assert ran >= 2
