@@ -34,11 +34,12 @@ HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {((256, 256, 64), (128, 64), 1): 269.4e6, ((256, 256, 64), (64, 128), 1): 269.4e6}
 
 
-def _algorithmic_bytes(w, gs_inputs):
+def _algorithmic_bytes(w, gs_inputs, out_dtype="f32"):
     es = 4 if w.dtype == "f32" else 2
+    eo = 4 if out_dtype == "f32" else 2
     if isinstance(w, gs_inputs.GemmWorkload):
-        return w.batch * (es * (w.M * w.K + w.K * w.N) + 4 * w.M * w.N)
-    return es * (w.n * w.c * w.h * w.w + w.k * w.c * w.r * w.s) + 4 * w.n * w.k * w.p * w.q
+        return w.batch * (es * (w.M * w.K + w.K * w.N) + eo * w.M * w.N)
+    return es * (w.n * w.c * w.h * w.w + w.k * w.c * w.r * w.s) + eo * w.n * w.k * w.p * w.q
 
 
 COLD_BYTES = 640 << 20     # operand sets rotated through in the cold-cache timing (Infinity Cache: 256 MB)
@@ -47,18 +48,18 @@ COLD_BYTES = 640 << 20     # operand sets rotated through in the cold-cache timi
 class Case:
     """One workload resident on the device with its constructed schedule."""
 
-    def __init__(self, gs, inputs, w, opts=None):
+    def __init__(self, gs, inputs, w, opts=None, out_dtype="f32"):
         import torch
         self.gs, self.w = gs, w
         self.is_gemm = isinstance(w, inputs.GemmWorkload)
         if self.is_gemm:
-            self.p = gs.gemm_problem(w.dtype, w.M, w.N, w.K, w.transA, w.transB, w.batch)
+            self.p = gs.gemm_problem(w.dtype, w.M, w.N, w.K, w.transA, w.transB, w.batch, out_dtype)
             self.a, self.b = gs.to_device(w.A, w.dtype), gs.to_device(w.B, w.dtype)
-            self.out = gs.empty_device((w.batch, w.M, w.N) if w.batch > 1 else (w.M, w.N))
+            self.out = gs.empty_device((w.batch, w.M, w.N) if w.batch > 1 else (w.M, w.N), out_dtype)
         else:
-            self.p = gs.conv_problem(w.dtype, w.n, w.c, w.h, w.w, w.k, w.r, w.s, w.stride, w.pad)
+            self.p = gs.conv_problem(w.dtype, w.n, w.c, w.h, w.w, w.k, w.r, w.s, w.stride, w.pad, out_dtype)
             self.a, self.b = gs.to_device(w.I, w.dtype), gs.to_device(w.W, w.dtype)
-            self.out = gs.empty_device((w.n, w.k, w.p, w.q))
+            self.out = gs.empty_device((w.n, w.k, w.p, w.q), out_dtype)
         t0 = time.perf_counter()
         self.sched = gs.construct(self.p, seed=0, opts=opts)
         self.construct_s = time.perf_counter() - t0
@@ -185,6 +186,32 @@ def _median_ms(fn, steps, warmup=5, batches=5):
         torch.cuda.synchronize()
         out.append(e0.elapsed_time(e1) / steps)
     return sorted(out)[len(out) // 2]
+
+
+def variant_rows(gs, inputs, steps):
+    """The benchmark shapes in their other stated forms: the 16-bit-input shapes with output in the input type
+    (half the store traffic, so another roofline), and the attention scores with K^T laid out in memory."""
+    import torch
+    cfgs = inputs.all_configs()
+    todo = [(cfgs[n], "f16") for n in ("cfg3_up", "cfg3_down", "cfg4", "cfg5_3x3", "cfg5_1x1s2")]
+    todo.append((inputs.config4_bmm_scores(materialised_kt=True), "f32"))
+    rows = []
+    for wl, out_dtype in todo:
+        c = Case(gs, inputs, wl, out_dtype=out_dtype)
+        m = c.time_median_ms(steps, 20)
+        nbytes = _algorithmic_bytes(wl, inputs, out_dtype)
+        tf = wl.flops / (m * 1e-3) / 1e12
+        ceiling = min(PEAK_TFLOPS[wl.dtype], wl.flops / nbytes * HBM_GBS / 1e3)
+        rows.append({"workload": wl.name, "out_dtype": out_dtype, "us": m * 1e3, "tflops": tf,
+                     "algorithmic_GBs": nbytes / (m * 1e-3) / 1e9, "roofline_ceiling_tflops": ceiling,
+                     "pct_of_roofline_ceiling": 100.0 * tf / ceiling, "kernel_id": c.sched.kernel_id,
+                     "schedule": "%dx%dx%d wave %dx%d stages %d direct %d" % (
+                         c.sched.tile[0][0], c.sched.tile[1][0], c.sched.tile[2][0], c.sched.tile[0][1],
+                         c.sched.tile[1][1], c.sched.stages, c.sched.direct_lds),
+                     "parity_rel_frobenius_sampled": c.parity(256)})
+        del c
+        torch.cuda.empty_cache()
+    return rows
 
 
 def operator_table_rows(gs, inputs):
@@ -385,6 +412,7 @@ def main():
             del c, wl
             torch.cuda.empty_cache()
         line["unbalanced_gemms"] = nxt
+        line["variants"] = variant_rows(gs, inputs, steps2)
         line["operator_table"] = operator_table_rows(gs, inputs)
         line["ablation"] = ablation(gs, inputs)
         line["cpu_baseline"] = cpu_baseline(w)

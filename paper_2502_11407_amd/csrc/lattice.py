@@ -70,6 +70,11 @@ def lattice():
         # 16-bit output variants
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "KC"))
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "NC"))
+        out.append(_inst(dt, dt, 256, 256, 64, 128, 64, 32, 1, 1, "KC", direct=1))
+        out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "KC", direct=1))
+        out.append(_inst(dt, dt, 128, 256, 64, 64, 64, 32, 1, 1, "NC"))
+        out.append(_inst(dt, dt, 256, 256, 64, 128, 64, 32, 1, 1, "NC"))
+        out.append(_inst(dt, dt, 256, 256, 64, 128, 64, 32, 1, 1, "NCS2"))
         out.append(_inst(dt, dt, 64, 64, 32, 32, 32, 16, 1, 1, "KC", vec=0))
         out.append(_inst(dt, dt, 64, 64, 32, 32, 32, 16, 1, 1, "NC", vec=0))
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "CONV"))
@@ -87,6 +92,8 @@ def lattice():
                                              (128, 128, 16, 32, 64, 1)]:
             out.append(_convp(dt, "f32", bm, bn, bkc, wm, wn, units, stages=1))
         out.append(_convp(dt, dt, 64, 128, 16, 32, 64, 1))
+        out.append(_convp(dt, dt, 64, 256, 16, 64, 64, 1, stages=1))
+        out.append(_convp(dt, dt, 128, 256, 16, 64, 64, 1, stages=1))
     for (bm, bn, bkc, wm, wn, units) in [(64, 128, 8, 32, 64, 1), (64, 64, 8, 32, 32, 1), (128, 128, 8, 64, 64, 2)]:
         out.append(_convp("f32", "f32", bm, bn, bkc, wm, wn, units))
     tiles32 = [
