@@ -483,7 +483,6 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     return (bj / PER) * (BN / C::VN) + wave_n * (C::WN / C::VN) + (bj % PER) * MB;
   };
   u32x4 fa[2][C::MBLK], fb[2][C::NBLK];
-  constexpr bool TRANS_ACC = C::BSRC != B_CONV;
   auto read_frags = [&](int st, int ks, int buf) {
     GENSOR_LDS char* abase = lds + st * C::STAGE_BYTES;
     GENSOR_LDS char* bbase = abase + C::A_BYTES;
@@ -539,10 +538,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     for (int bi = 0; bi < C::MBLK; ++bi)
 #pragma unroll
       for (int bj = 0; bj < C::NBLK; ++bj) {
-        // GEMM / BMM accumulate the transposed block (B fragment as the first operand): a lane
-        // then holds 4 consecutive columns of one row of C, which the epilogue stores as one vector
-        if constexpr (TRANS_ACC) MF::run(fb[buf][bj], fa[buf][bi], acc[bi][bj]);
-        else MF::run(fa[buf][bi], fb[buf][bj], acc[bi][bj]);
+        MF::run(fa[buf][bi], fb[buf][bj], acc[bi][bj]);
       }
   };
 
@@ -686,11 +682,13 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   }
 
   // ---- epilogue: C = alpha * acc + beta * C through a buffer descriptor that starts at this
-  // tile's first element; rows outside the matrix fall out of its range.  With the transposed
-  // accumulation lane l of a 32x32 block holds row l%32 and, for g = 0..3, the 4 consecutive
-  // columns 8g + 4*(l/32) + {0..3} in acc[4g..4g+3]; in a 16x16 block row l%16 and columns
-  // 4*(l/16) + {0..3}.  (The convolution path keeps the untransposed layout: column l%MB, rows
-  // 8*(v/4) + 4*(l/32) + v%4, or 4*(l/16) + v.)
+  // tile's first element; rows outside the matrix fall out of its range, columns beyond it are
+  // sent out of range explicitly (they would alias the next row).  Lane l of a 32x32 block holds
+  // column l%32 and rows 8*(v/4) + 4*(l/32) + v%4 in acc[v] (16x16: column l%16, rows 4*(l/16) + v),
+  // so one element store of a wave covers two whole 128-byte row segments of C (four 64-byte
+  // ones for 16x16 blocks).  Accumulating the transposed block instead, for 16-byte vector stores
+  // of four columns per lane, measured slower everywhere (32 rows x 32 bytes per instruction:
+  // -3 % on the 4096^3 GEMM, -9 % on 8192x3072x768, -11 % on the store-bound K = 64 shapes).
   typedef typename C::OutT OutT;
   constexpr int OS = ElemSize<OutT>::value;
   char* Cb = (char*)args.C + (int64_t)bidx * args.strideC * OS;
@@ -716,64 +714,29 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(Cb + ((int64_t)m0 * args.ldc + n0) * OS), 0,
         clamp_records(((int64_t)(rows_valid - 1) * args.ldc + cols_valid) * OS), RSRC_FLAGS);
-    constexpr int GROUPS = MF::NACC / 4;
 #pragma unroll
     for (int bi = 0; bi < C::MBLK; ++bi)
 #pragma unroll
       for (int bj = 0; bj < C::NBLK; ++bj) {
-        const int row = block_row(bi) + frow;
+        const int col = block_col(bj) + frow;
+        const bool col_ok = col < cols_valid;
 #pragma unroll
-        for (int g = 0; g < GROUPS; ++g) {
-          const int col = block_col(bj) + 8 * g + 4 * fgrp;
-          const uint32_t off = (uint32_t)((row * (int)args.ldc + col) * OS);
-          float val[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) val[e] = alpha * acc[bi][bj][4 * g + e];
-          if (col + 3 < cols_valid) {
-            if constexpr (OS == 4) {
-              if (beta != 0.f) {
-                const u32x4 old = __builtin_amdgcn_raw_buffer_load_b128(rc, off, 0, 0);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) val[e] += beta * as_f32(old[e]);
-              }
-              u32x4 o;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) o[e] = __builtin_bit_cast(uint32_t, val[e]);
-              __builtin_amdgcn_raw_buffer_store_b128(o, rc, off, 0, 0);
-            } else {
-              uint16_t h[4];
-              if (beta != 0.f) {
-                const u32x2 old = __builtin_amdgcn_raw_buffer_load_b64(rc, off, 0, 0);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const uint16_t ob = (uint16_t)(old[e >> 1] >> ((e & 1) * 16));
-                  val[e] += beta * to_float<OutT>(&ob, 0);
-                }
-              }
-#pragma unroll
-              for (int e = 0; e < 4; ++e) store_out<OutT>(&h[e], 0, val[e]);
-              u32x2 o = {(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
-              __builtin_amdgcn_raw_buffer_store_b64(o, rc, off, 0, 0);
-            }
+        for (int v = 0; v < MF::NACC; ++v) {
+          const int r = (MB == 32) ? 8 * (v / 4) + 4 * fgrp + (v % 4) : 4 * fgrp + v;
+          const int row = block_row(bi) + r;
+          const uint32_t off = col_ok ? (uint32_t)((row * (int)args.ldc + col) * OS) : OOB;
+          float x = alpha * acc[bi][bj][v];
+          if constexpr (OS == 4) {
+            if (beta != 0.f) x += beta * as_f32(__builtin_amdgcn_raw_buffer_load_b32(rc, off, 0, 0));
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, x), rc, off, 0, 0);
           } else {
-            // ragged right edge: element by element, columns beyond the matrix sent out of range
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const uint32_t eo = (col + e < cols_valid) ? off + e * OS : OOB;
-              float x = val[e];
-              if constexpr (OS == 4) {
-                if (beta != 0.f) x += beta * as_f32(__builtin_amdgcn_raw_buffer_load_b32(rc, eo, 0, 0));
-                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, x), rc, eo, 0, 0);
-              } else {
-                if (beta != 0.f) {
-                  const uint16_t old = __builtin_amdgcn_raw_buffer_load_b16(rc, eo, 0, 0);
-                  x += beta * to_float<OutT>(&old, 0);
-                }
-                uint16_t bits;
-                store_out<OutT>(&bits, 0, x);
-                __builtin_amdgcn_raw_buffer_store_b16(bits, rc, eo, 0, 0);
-              }
+            if (beta != 0.f) {
+              const uint16_t old = __builtin_amdgcn_raw_buffer_load_b16(rc, off, 0, 0);
+              x += beta * to_float<OutT>(&old, 0);
             }
+            uint16_t bits;
+            store_out<OutT>(&bits, 0, x);
+            __builtin_amdgcn_raw_buffer_store_b16(bits, rc, off, 0, 0);
           }
         }
       }
