@@ -479,6 +479,8 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     t_sync = nk * t_ktile
     if stages > 2 and view.bsrc == 0:
         t_sync = t_sync / (stages - 1)
+    if stages == 1:
+        t_sync = t_sync + (nk - 1.0) * 4.0 * t_ktile       # a single buffer: each further tile waits out its own fetch
     t_main = max(t_mfma, t_lds, t_feed) / overlap + t_sync
     hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units
     t_epi = bm * bn * eo / (0.8 * hbm_bw_cu)

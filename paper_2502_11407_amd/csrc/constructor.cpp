@@ -361,6 +361,7 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   const double nk = std::ceil((double)v.K / bk);
   double t_sync = nk * t_ktile;
   if (stages > 2 && v.bsrc == B_KC) t_sync = t_sync / (stages - 1);
+  if (stages == 1) t_sync = t_sync + (nk - 1.0) * 4.0 * t_ktile;       // a single buffer: each further tile waits out its own fetch
   t_main = t_main / overlap + t_sync;
   const double hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units;
   const double t_epi = bm * bn * eo / (0.8 * hbm_bw_cu);

@@ -67,6 +67,10 @@ def lattice():
         # for k-contiguous operands only
         for (bm, bn) in ((128, 256), (256, 128)):
             out.append(_inst(dt, "f32", bm, bn, 64, 64, 64, 32, 1, 1, "KC", stages=3, direct=1))
+        # one LDS stage: half the LDS, twice the resident workgroups, for contractions of a single k tile
+        for bsrc in ("KC", "NC"):
+            for (bm, bn, wm, wn) in ((128, 128, 64, 64), (128, 64, 64, 32)):
+                out.append(_inst(dt, "f32", bm, bn, 64, wm, wn, 32, 1, 1, bsrc, stages=1))
         # 16-bit output variants
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "KC"))
         out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, 1, 1, "NC"))
