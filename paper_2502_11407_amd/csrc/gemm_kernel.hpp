@@ -368,7 +368,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   // ---- fetch the k tile starting at k0: into registers, or straight into LDS stage `st`.
   // In a k-contiguous row a chunk beyond K would alias the next row, so those lanes are
   // sent out of range; this can only happen in the last k tile.
-  auto fetch_a = [&](int k0, int st) {
+  auto fetch_a = [&](int k0, int st, int part = 0, int parts = 1) {
     const bool full = args.K - k0 >= BK;
     if constexpr (SCALAR_A) {
 #pragma unroll
@@ -383,6 +383,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 #pragma unroll
       for (int i = 0; i < C::A_LOADS; ++i) {
         if (C::A_CHUNKS % C::THREADS != 0 && tid + i * C::THREADS >= C::A_CHUNKS) break;
+        if (i * parts < part * C::A_LOADS || i * parts >= (part + 1) * C::A_LOADS) continue;
         const uint32_t off = (full || (int)a_kch[i] < args.K - k0) ? a_voff[i] : OOB;
         if constexpr (C::DIRECT)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (GENSOR_LDS void*)(lds + st * C::STAGE_BYTES + (i * C::THREADS + wave * 64) * 16),
@@ -392,7 +393,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       }
     }
   };
-  auto fetch_b = [&](int k0, int st) {
+  auto fetch_b = [&](int k0, int st, int part = 0, int parts = 1) {
     const bool full = args.K - k0 >= BK;
     if constexpr (SCALAR_B) {
 #pragma unroll
@@ -413,6 +414,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 #pragma unroll
       for (int i = 0; i < C::B_LOADS; ++i) {
         if (C::B_CHUNKS % C::THREADS != 0 && tid + i * C::THREADS >= C::B_CHUNKS) break;
+        if (i * parts < part * C::B_LOADS || i * parts >= (part + 1) * C::B_LOADS) continue;
         uint32_t off = b_voff[i];
         if constexpr (C::BSRC == B_KC) off = (full || (int)b_kch[i] < args.K - k0) ? off : OOB;
         if constexpr (C::DIRECT) {
@@ -556,6 +558,20 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     __builtin_amdgcn_sched_barrier(0);
   };
 
+  // the same with the global loads of this step spread between the MFMAs as well
+  auto interleave_vmem = [&]() {
+    constexpr int NM = C::MBLK * C::NBLK * (ES == 4 ? 4 : 1);
+    constexpr int NR = C::MBLK + C::NBLK * (C::BSRC == B_KC ? 1 : (ES == 4 ? 4 : 2));
+    constexpr int RPM = (NR + NM - 1) / NM;
+#pragma unroll
+    for (int i = 0; i < NM; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);   // LDS reads
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // one global load
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
   // ---- main loop over k tiles.  Tile kt+1 is fetched while tile kt is multiplied; its
   // first fragments are read right after the barrier, under the MFMAs of the last k step
   // of tile kt, so that the barrier and the LDS latency are covered by matrix work.
@@ -630,12 +646,19 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     auto k_tile = [&](int kt, auto more_tag) {
       constexpr bool more = decltype(more_tag)::value;
       const int cur = kt & 1, nxt = cur ^ 1;
-      if constexpr (more) {
-        fetch_a((kt + 1) * BK, nxt);
-        fetch_b((kt + 1) * BK, nxt);
-      }
+      // Wave tiles of eight and more MFMAs per k step issue the direct loads of the next tile over the
+      // first two k steps, one between MFMAs, instead of in one burst at the top: with one such wave
+      // per SIMD the burst is time no MFMA runs (256x256 tile of four 128x128 waves: 124 -> 116 us;
+      // two 128x64 waves per SIMD gain 1 %; 64x64 wave tiles lose 1-8 % and keep the burst).
+      constexpr int FS = (C::DIRECT && C::KSTEPS >= 4 && C::MBLK * C::NBLK >= 8) ? 2 : 1;
 #pragma unroll
       for (int ks = 0; ks < C::KSTEPS; ++ks) {
+        if constexpr (more) {
+          if (ks < FS) {
+            fetch_a((kt + 1) * BK, nxt, ks, FS);
+            fetch_b((kt + 1) * BK, nxt, ks, FS);
+          }
+        }
         if (ks + 1 < C::KSTEPS) {
           read_frags(cur, ks + 1, (ks + 1) & 1);
         } else if constexpr (more) {
@@ -645,7 +668,8 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
           read_frags(nxt, 0, 0);
         }
         mma(ks & 1);
-        interleave();
+        if (FS > 1 && more && ks < FS) interleave_vmem();
+        else interleave();
       }
     };
     read_frags(0, 0, 0);
