@@ -472,6 +472,8 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     overlap = 0.7 + 0.1 * min(resident * nwaves / hw.simds_per_cu, 3.0)
     if direct and view.bsrc == 0:          # measured: direct staging pays for k-contiguous operands only
         overlap += 0.05
+    if direct and view.bsrc == 0 and stages == 2 and wm * wn >= 128 * 128 and bk == 4 * kg:   # the two-steps-ahead schedule of the one-wave-per-SIMD tiles (k-contiguous operands: measured)
+        overlap += 0.12
     # every k tile boundary (barrier, refill of the fragment pipeline) exposes a share of the memory latency
     # (a ring of three and more stages keeps more tiles in flight; measured to pay for k-contiguous operands)
     t_ktile = 0.25 * hw.latency_ns[0] * 1e-3

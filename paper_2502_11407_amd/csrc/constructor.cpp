@@ -352,6 +352,7 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   if (par > 3.0) par = 3.0;
   double overlap = 0.7 + 0.1 * par;
   if (direct && v.bsrc == B_KC) overlap += 0.05;      // measured: direct staging pays for k-contiguous operands only
+  if (direct && v.bsrc == B_KC && stages == 2 && wm * wn >= 128 * 128 && bk == 4 * kg) overlap += 0.12;   // the two-steps-ahead schedule of the one-wave-per-SIMD tiles (k-contiguous operands: measured)
   double t_main = t_mfma;
   if (t_lds > t_main) t_main = t_lds;
   if (t_feed > t_main) t_main = t_feed;
