@@ -384,7 +384,8 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       for (int i = 0; i < C::A_LOADS; ++i) {
         if (C::A_CHUNKS % C::THREADS != 0 && tid + i * C::THREADS >= C::A_CHUNKS) break;
         if (i * parts < part * C::A_LOADS || i * parts >= (part + 1) * C::A_LOADS) continue;
-        const uint32_t off = (full || (int)a_kch[i] < args.K - k0) ? a_voff[i] : OOB;
+        // (direct staging is only launched for K a multiple of BK: every tile is full)
+        const uint32_t off = (C::DIRECT || full || (int)a_kch[i] < args.K - k0) ? a_voff[i] : OOB;
         if constexpr (C::DIRECT)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (GENSOR_LDS void*)(lds + st * C::STAGE_BYTES + (i * C::THREADS + wave * 64) * 16),
                                                    16, off, 0, 0, 0);
@@ -416,7 +417,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         if (C::B_CHUNKS % C::THREADS != 0 && tid + i * C::THREADS >= C::B_CHUNKS) break;
         if (i * parts < part * C::B_LOADS || i * parts >= (part + 1) * C::B_LOADS) continue;
         uint32_t off = b_voff[i];
-        if constexpr (C::BSRC == B_KC) off = (full || (int)b_kch[i] < args.K - k0) ? off : OOB;
+        if constexpr (C::BSRC == B_KC && !C::DIRECT) off = (full || (int)b_kch[i] < args.K - k0) ? off : OOB;
         if constexpr (C::DIRECT) {
           __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (GENSOR_LDS void*)(lds + st * C::STAGE_BYTES + C::A_BYTES + (i * C::THREADS + wave * 64) * 16),
                                                    16, off, 0, 0, 0);
@@ -564,16 +565,26 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     __builtin_amdgcn_sched_barrier(0);
   };
 
-  // the same with the global loads of this step spread between the MFMAs as well
-  auto interleave_vmem = [&]() {
+  // the same with the global loads of this step between the MFMAs as well.  One wave per SIMD
+  // (`separate`): the fragment reads in front of the first MFMAs, then one load per MFMA, so that
+  // no gap between two MFMAs has to issue both a read and a load.  Two waves per SIMD measure better
+  // with a load and a read per gap, loads first.
+  auto interleave_vmem = [&](auto separate_tag) {
+    constexpr bool separate = decltype(separate_tag)::value;
     constexpr int NM = C::MBLK * C::NBLK * (ES == 4 ? 4 : 1);
     constexpr int NR = C::MBLK + C::NBLK * (C::BSRC == B_KC ? 1 : (ES == 4 ? 4 : 2));
     constexpr int RPM = (NR + NM - 1) / NM;
+    constexpr int READ_SLOTS = (NR + RPM - 1) / RPM;
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);   // LDS reads
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // one global load
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+      if constexpr (separate) {
+        if (i < READ_SLOTS) __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);   // LDS reads
+        else __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                     // one global load
+      } else {
+        __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                            // one MFMA
     }
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -606,24 +617,24 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       if constexpr (has_next) {
         wait_deposits();
         __syncthreads();
+        read_frags(nxt, 0, 0);
         if constexpr (has_fetch) {
           fetch_a((kt + 2) * BK, cur, 0, 2);
           fetch_b((kt + 2) * BK, cur, 0, 2);
         }
-        read_frags(nxt, 0, 0);
       }
       mma(2);
-      if constexpr (has_fetch) interleave_vmem();
+      if constexpr (has_fetch) interleave_vmem(std::true_type{});
       else interleave();
       if constexpr (has_next) {
+        read_frags(nxt, 1, 1);
         if constexpr (has_fetch) {
           fetch_a((kt + 2) * BK, cur, 1, 2);
           fetch_b((kt + 2) * BK, cur, 1, 2);
         }
-        read_frags(nxt, 1, 1);
       }
       mma(3);
-      if constexpr (has_fetch) interleave_vmem();
+      if constexpr (has_fetch) interleave_vmem(std::true_type{});
       else interleave();
     };
     if (nk > 1) {
@@ -719,7 +730,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
           read_frags(nxt, 0, 0);
         }
         mma(ks & 1);
-        if (FS > 1 && more && ks < FS) interleave_vmem();
+        if (FS > 1 && more && ks < FS) interleave_vmem(std::false_type{});
         else interleave();
       }
     };
