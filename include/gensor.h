@@ -71,7 +71,7 @@ typedef struct {
   int32_t kernel_id;          /* index of the compiled instance; filled by gensor_construct */
   int32_t tile[3][3];
   int32_t vthread[2];         /* V for m and n: the wave tile is split into V strided pieces */
-  int32_t stages;             /* LDS buffers in flight: 1 or 2 */
+  int32_t stages;             /* LDS buffers: 1, 2, or a ring of 3 (two k tiles in flight) */
   int32_t unroll;             /* MFMA k-steps unrolled per LDS stage = BK / (k per fragment) */
   int32_t vec_bytes;          /* width of one global access: 16, or the element size (scalar path) */
   int32_t direct_lds;         /* 1: global->LDS loads bypass registers */
