@@ -143,12 +143,13 @@ __global__ __launch_bounds__(256) void gemv_scalar_kernel(const char* A, int64_t
 // are not 16-byte aligned or whose rows do not fit the LDS span.
 // ---------------------------------------------------------------------------------------
 constexpr int POOL_SPAN_BYTES = 32768;
+constexpr int POOL_VECS = (POOL_SPAN_BYTES + 16 + 15) / 16 / 256 + 1;     // 16-byte vectors per thread covering span + skew
 
 template <typename T, typename OutT>
 __global__ __launch_bounds__(256) void avgpool_lds_kernel(const char* in, void* out, int64_t in_bytes, int planes, int H, int W, int P,
                                                           int Q, int F, int S, int planes_per_wg, int rows_per_wg, int chunks_per_plane) {
   constexpr int ES = ElemSize<T>::value;
-  __shared__ __attribute__((aligned(16))) char span[POOL_SPAN_BYTES + 16];
+  extern __shared__ __attribute__((aligned(16))) char span[];      // the launch sizes it to this problem's span (+ skew)
   const int tid = threadIdx.x;
   const int group = blockIdx.x / chunks_per_plane, chunk = blockIdx.x - group * chunks_per_plane;
   const int plane0 = group * planes_per_wg;
@@ -161,20 +162,31 @@ __global__ __launch_bounds__(256) void avgpool_lds_kernel(const char* in, void* 
   const int64_t b0 = e0 * ES, a0 = b0 & ~(int64_t)15;
   const int skew = (int)(b0 - a0);                            // bytes before the first element in LDS
   const int nvec = (skew + len * ES + 15) / 16;
-  for (int v = tid; v < nvec; v += 256) {
+  // all of a thread's vectors are requested before the first one is written to LDS (one memory
+  // round trip per workgroup instead of one per vector); the span holds at most POOL_VECS per thread
+  u32x4 d[POOL_VECS];
+#pragma unroll
+  for (int i = 0; i < POOL_VECS; ++i) {
+    const int v = tid + i * 256;
     const int64_t addr = a0 + (int64_t)v * 16;
-    u32x4 d = {0u, 0u, 0u, 0u};
-    if (addr + 16 <= in_bytes) {
-      d = *(const u32x4*)(in + addr);
-    } else {                                                  // last vector of the tensor: element by element
-      for (int e = 0; e < 16 / ES; ++e) {
-        if (addr + (e + 1) * ES <= in_bytes) {
-          if constexpr (ES == 4) d[e] = *(const uint32_t*)(in + addr + e * 4);
-          else d[e >> 1] |= (uint32_t)*(const uint16_t*)(in + addr + e * 2) << ((e & 1) * 16);
+    d[i] = u32x4{0u, 0u, 0u, 0u};
+    if (v < nvec) {
+      if (addr + 16 <= in_bytes) {
+        d[i] = *(const u32x4*)(in + addr);
+      } else {                                                // last vector of the tensor: element by element
+        for (int e = 0; e < 16 / ES; ++e) {
+          if (addr + (e + 1) * ES <= in_bytes) {
+            if constexpr (ES == 4) d[i][e] = *(const uint32_t*)(in + addr + e * 4);
+            else d[i][e >> 1] |= (uint32_t)*(const uint16_t*)(in + addr + e * 2) << ((e & 1) * 16);
+          }
         }
       }
     }
-    *(u32x4*)(span + v * 16) = d;
+  }
+#pragma unroll
+  for (int i = 0; i < POOL_VECS; ++i) {
+    const int v = tid + i * 256;
+    if (v < nvec) *(u32x4*)(span + v * 16) = d[i];
   }
   __syncthreads();
   const int per_plane = nrows * Q;
@@ -241,6 +253,9 @@ hipError_t launch_pool(const void* in, void* out, int64_t planes, int64_t h, int
     G = POOL_SPAN_BYTES / plane_bytes;
     const int64_t cap = (8192 + P * Q - 1) / (P * Q);          // keep a workgroup to a few thousand outputs
     if (G > cap) G = cap;
+    // enough workgroups to keep every CU's resident set (LDS is sized to the span) turning over several times
+    const int64_t spread = planes / (256 * 8 * 4);
+    if (G > spread) G = spread > 1 ? spread : 1;
     if (G > planes) G = planes;
     R = P;
     cpp = 1;
@@ -252,7 +267,9 @@ hipError_t launch_pool(const void* in, void* out, int64_t planes, int64_t h, int
   }
   const int64_t groups = G ? (planes + G - 1) / G * cpp : 0;
   if (G && groups <= INT32_MAX && planes <= INT32_MAX) {
-    hipLaunchKernelGGL((avgpool_lds_kernel<T, OutT>), dim3((unsigned)groups), dim3(256), 0, st, (const char*)in, out,
+    const int64_t span_elems = cpp == 1 ? G * h * w : ((R - 1) * s + f) * w;
+    const size_t lds_bytes = (size_t)((span_elems * ES + 15 + 15) / 16 * 16 + 16);      // span + skew, whole vectors
+    hipLaunchKernelGGL((avgpool_lds_kernel<T, OutT>), dim3((unsigned)groups), dim3(256), lds_bytes, st, (const char*)in, out,
                        planes * plane_bytes, (int)planes, (int)h, (int)w, (int)P, (int)Q, (int)f, (int)s, (int)G, (int)R, (int)cpp);
   } else {
     const int64_t total = planes * P * Q;
