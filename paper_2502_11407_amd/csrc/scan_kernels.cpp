@@ -54,17 +54,26 @@ __global__ __launch_bounds__(256) void gemv_vec_kernel(const char* A, int64_t ld
     const int pn = min(PANEL, N - p0);                 // elements of x in this panel
     const int full = pn / EPC;                         // whole vectors
     __syncthreads();                                   // the previous panel has been consumed
-    for (int c = tid; c < (pn + EPC - 1) / EPC; c += 256) {
-      u32x4 v = {0u, 0u, 0u, 0u};
+    // all of a thread's vectors of the panel are requested before the first is written to LDS
+    constexpr int XV = GEMV_PANEL_BYTES / 16 / 256;
+    u32x4 xv[XV];
+#pragma unroll
+    for (int i = 0; i < XV; ++i) {
+      const int c = tid + i * 256;
+      xv[i] = u32x4{0u, 0u, 0u, 0u};
       if (c < full) {
-        v = *(const u32x4*)(x + ((int64_t)p0 + (int64_t)c * EPC) * ES);
-      } else {                                         // ragged end of x: element by element, zero beyond N
+        xv[i] = *(const u32x4*)(x + ((int64_t)p0 + (int64_t)c * EPC) * ES);
+      } else if (c < (pn + EPC - 1) / EPC) {           // ragged end of x: element by element, zero beyond N
         for (int e = 0; e < pn - full * EPC; ++e) {
-          if constexpr (ES == 4) v[e] = ((const uint32_t*)x)[p0 + c * EPC + e];
-          else v[e >> 1] |= (uint32_t)((const uint16_t*)x)[p0 + c * EPC + e] << ((e & 1) * 16);
+          if constexpr (ES == 4) xv[i][e] = ((const uint32_t*)x)[p0 + c * EPC + e];
+          else xv[i][e >> 1] |= (uint32_t)((const uint16_t*)x)[p0 + c * EPC + e] << ((e & 1) * 16);
         }
       }
-      *(u32x4*)(xs + c * 16) = v;
+    }
+#pragma unroll
+    for (int i = 0; i < XV; ++i) {
+      const int c = tid + i * 256;
+      if (c < (pn + EPC - 1) / EPC) *(u32x4*)(xs + c * 16) = xv[i];
     }
     __syncthreads();
     int c = lane;
