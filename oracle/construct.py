@@ -422,10 +422,10 @@ def predict_patch_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, stages) -> floa
     lds_bw = hw.bandwidth_gbs[1] * 1e3 / hw.compute_units
     t_lds = RS * ksteps * ((wm // mb) + (wn // mb)) * 1024.0 * nwaves / lds_bw * resident
     l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units
-    t_feed = (rows * w * bk * e + bm * RS * bk * e) / l2_bw * resident
-    t_fixed = (hw.latency_ns[0] + 2.0 * hw.latency_ns[1]) * 1e-3            # fetch issue, commit, two barriers
+    t_feed = (rows * w * bk * e + bm * RS * bk * e) / (0.5 * l2_bw)      # 16-byte gathers: half the L2 rate; hidden by the other resident workgroups
+    t_fixed = (0.75 * hw.latency_ns[0] + 1.5 * hw.latency_ns[1]) * 1e-3     # fetch issue, commit, two barriers
     t_stage = t_mfma + t_lds + t_feed + t_fixed
-    t_pro = (3.0 * hw.latency_ns[0] + 10.0 * hw.latency_ns[1]) * 1e-3       # index set-up, first fetch at full latency, zero fill
+    t_pro = (2.0 * hw.latency_ns[0] + 6.0 * hw.latency_ns[1]) * 1e-3        # index set-up, first fetch at full latency, zero fill
     t_epi = bm * bn * eo / (0.6 * hw.bandwidth_gbs[0] * 1e3 / hw.compute_units)
     t_cu = rounds * (t_pro + nst * t_stage + t_epi)
     bytes_total = e * (n * c * h * w + view.M * view.K) + eo * view.M * view.N

@@ -303,10 +303,10 @@ double predict_patch(const GemmView& v, const gensor_hw& hw, int bm, int bn, int
   const double lds_bw = hw.bandwidth_gbs[1] * 1e3 / hw.compute_units;
   const double t_lds = (double)(RS * ksteps * ((wm / mb) + (wn / mb))) * 1024.0 * nwaves / lds_bw * resident;
   const double l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units;
-  const double t_feed = (double)(rows * v.cw * bk * e + bm * RS * bk * e) / l2_bw * resident;
-  const double t_fixed = (hw.latency_ns[0] + 2.0 * hw.latency_ns[1]) * 1e-3;
+  const double t_feed = (double)(rows * v.cw * bk * e + bm * RS * bk * e) / (0.5 * l2_bw);     // 16-byte gathers: half the L2 rate; hidden by the other resident workgroups
+  const double t_fixed = (0.75 * hw.latency_ns[0] + 1.5 * hw.latency_ns[1]) * 1e-3;
   const double t_stage = t_mfma + t_lds + t_feed + t_fixed;
-  const double t_pro = (3.0 * hw.latency_ns[0] + 10.0 * hw.latency_ns[1]) * 1e-3;
+  const double t_pro = (2.0 * hw.latency_ns[0] + 6.0 * hw.latency_ns[1]) * 1e-3;
   const double t_epi = (double)(bm * bn * eo) / (0.6 * hw.bandwidth_gbs[0] * 1e3 / hw.compute_units);
   const double t_cu = rounds * (t_pro + nst * t_stage + t_epi);
   const double bytes_total = (double)(e * (v.cn * v.cc * v.ch * v.cw + v.M * v.K) + eo * v.M * v.N);

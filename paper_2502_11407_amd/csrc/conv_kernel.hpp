@@ -85,7 +85,10 @@ __global__ __launch_bounds__(256) void subsample_input(const void* in, void* out
   }
 }
 
-template <typename C>
+// FMODE, how the filters are reordered on the way into the tile, is a template parameter: with all
+// three routes in one kernel the register allocation is the union of theirs (250 VGPRs, spills to
+// scratch) and every convolution shape measured ran 14 % slower.
+template <typename C, int FMODE>
 __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs args) {
   typedef typename C::T T;
   typedef Mfma<T, C::MB> MF;
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
   // fmode 1 (1x1) and 0 (other): vector v of this thread is, on the way in, the v-th 16-byte
   // piece of a filter row's contiguous (channel, tap) run of this stage and, on the way out,
   // one 16-byte channel group of one tap of a filter row of the tile.
-  const int fmode = RS == 9 ? 2 : (RS == 1 ? 1 : 0);
+  constexpr int fmode = FMODE;                       // 2: R*S = 9, 1: R*S = 1, 0: anything else (the launcher picks)
   const int a_vec_per_row = RS * C::OCT;
   const int a_vecs = BM * a_vec_per_row;
   constexpr int a_units = BM * C::OCT;
