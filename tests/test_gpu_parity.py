@@ -534,24 +534,62 @@ def test_shape_changes_reconstruct_within_a_latency_budget(gs):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("k_tiles", [1, 2, 3, 4, 7])
-def test_ring_staged_instances_across_k_depths(gs, k_tiles):
-    """Instances with three and more LDS stages: fewer k tiles than the ring holds (every fetch is in the
-    prologue), exactly as many, and enough for the steady state, each with ragged m and n, bit-exact on integers."""
+def test_multi_tile_schedules_across_k_depths(gs, k_tiles):
+    """Instances whose loop looks further ahead than one k tile or one k step (rings of three LDS stages; the
+    one-wave-per-SIMD tiles that read fragments two k steps ahead and fetch two tiles ahead): fewer k tiles than
+    the look-ahead (everything happens in the prologue and the peeled tiles), exactly as many, and enough for
+    the steady-state body, each with ragged m and n, bit-exact on integers."""
     ran = 0
     for idx in range(gs.num_instances()):
         for dt in ("f16", "bf16"):
-            p0 = gs.gemm_problem(dt, 64, 64, 64, 0, 1, 1, "f32")
-            s = gs.instance_schedule(idx, p0)
-            if s is None or s.stages <= 2:
-                continue
-            bm, bn, bk = s.tile[0][0], s.tile[1][0], s.tile[2][0]
-            M, N, K = 2 * bm + 17, bn + 8, k_tiles * bk
-            print(f"instance {idx} {dt} stages {s.stages} tile {bm}x{bn}x{bk} K={K}", flush=True)
-            A = inputs.small_ints(500 + idx, (M, K), dt, -2, 2)
-            B = inputs.small_ints(600 + idx, (N, K), dt, -2, 2)
-            want = ops.gemm(A, B, dt, transB=1)
-            got = run_gemm(gs, dt, M, N, K, 1, s, A, B)
-            assert np.abs(want).max() < 2048
-            assert np.array_equal(got, want), f"instance {idx} K={K}: max abs diff {np.abs(got - want).max()}"
-            ran += 1
-    assert ran >= 2
+            for tb in (1, 0):
+                p0 = gs.gemm_problem(dt, 64, 64, 64, 0, tb, 1, "f32")
+                s = gs.instance_schedule(idx, p0)
+                if s is None:
+                    continue
+                deep = s.direct_lds and s.tile[0][1] * s.tile[1][1] >= 128 * 128
+                if s.stages <= 2 and not deep:
+                    continue
+                bm, bn, bk = s.tile[0][0], s.tile[1][0], s.tile[2][0]
+                M, N, K = 2 * bm + 17, bn + 8, k_tiles * bk
+                print(f"instance {idx} {dt} transB={tb} stages {s.stages} tile {bm}x{bn}x{bk} K={K}", flush=True)
+                A = inputs.small_ints(500 + idx, (M, K), dt, -2, 2)
+                B = inputs.small_ints(600 + idx, (N, K) if tb else (K, N), dt, -2, 2)
+                want = ops.gemm(A, B, dt, transB=tb)
+                got = run_gemm(gs, dt, M, N, K, tb, s, A, B)
+                assert np.abs(want).max() < 2048
+                assert np.array_equal(got, want), f"instance {idx} K={K}: max abs diff {np.abs(got - want).max()}"
+                ran += 1
+    assert ran >= 6
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["cfg3_up", "cfg4", "cfg5_3x3", "cfg5_1x1s2"])
+def test_benchmark_shapes_with_output_in_the_input_type(gs, name):
+    """The 16-bit-input benchmark shapes with fp16 output (rounded once from the fp32 accumulator), full size,
+    constructed schedule, sampled entries against the oracle."""
+    import torch
+    w = inputs.all_configs()[name]
+    if isinstance(w, inputs.GemmWorkload):
+        p = gs.gemm_problem(w.dtype, w.M, w.N, w.K, w.transA, w.transB, w.batch, "f16")
+        out = gs.empty_device((w.batch, w.M, w.N) if w.batch > 1 else (w.M, w.N), "f16")
+        out.fill_(float("nan"))
+        dA, dB = gs.to_device(w.A, w.dtype), gs.to_device(w.B, w.dtype)
+        (gs.bmm if w.batch > 1 else gs.gemm)(p, dA, dB, out, 1.0, 0.0, None)
+        co = inputs.sample_indices(11, (w.batch, w.M, w.N), 400)
+        want = ops.bmm_at(w.A, w.B, w.dtype, co, transA=w.transA, transB=w.transB)
+        o3 = out if w.batch > 1 else out[None]
+        idx = torch.from_numpy(co).cuda()
+        got = o3[idx[:, 0], idx[:, 1], idx[:, 2]]
+    else:
+        p = gs.conv_problem(w.dtype, w.n, w.c, w.h, w.w, w.k, w.r, w.s, w.stride, w.pad, "f16")
+        out = gs.empty_device((w.n, w.k, w.p, w.q), "f16")
+        out.fill_(float("nan"))
+        gs.conv2d(p, gs.to_device(w.I, w.dtype), gs.to_device(w.W, w.dtype), out, None, gs.conv_workspace(p))
+        co = inputs.sample_indices(11, (w.n, w.k, w.p, w.q), 400)
+        want = ops.conv2d_at(w.I, w.W, w.dtype, co, stride=w.stride, pad=w.pad)
+        idx = torch.from_numpy(co).cuda()
+        got = out[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+    torch.cuda.synchronize()
+    assert not torch.isnan(out).any()
+    assert ops.rel_frobenius(got.double().cpu().numpy(), want) <= 2e-3
