@@ -593,3 +593,54 @@ def test_benchmark_shapes_with_output_in_the_input_type(gs, name):
     torch.cuda.synchronize()
     assert not torch.isnan(out).any()
     assert ops.rel_frobenius(got.double().cpu().numpy(), want) <= 2e-3
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_random_gemm_shapes_with_constructed_schedules(gs, dtype):
+    """Seeded random extents, layouts, batch counts and scalars, each with the schedule the constructor picks
+    for it: whatever instance that is (vector or element loads, any tile) must be bit-exact on integers."""
+    rng = np.random.default_rng(20250211)
+    for case in range(24):
+        M, N, K = (int(x) for x in rng.integers(1, 420, size=3))
+        if case % 3 == 0:                       # whole 16-byte chunks: the vector paths
+            N, K = max(8, N // 8 * 8), max(8, K // 8 * 8)
+        tb = int(rng.integers(0, 2))
+        batch = int(rng.integers(1, 4))
+        alpha, beta = float(rng.integers(-2, 3)), float(rng.integers(-1, 2))
+        print(f"case {case}: {dtype} {batch}x{M}x{N}x{K} transB={tb} alpha={alpha} beta={beta}", flush=True)
+        A = inputs.small_ints(700 + case, (batch, M, K) if batch > 1 else (M, K), dtype, -2, 2)
+        B = inputs.small_ints(800 + case, ((batch, N, K) if tb else (batch, K, N)) if batch > 1 else ((N, K) if tb else (K, N)),
+                              dtype, -2, 2)
+        C0 = inputs.small_ints(900 + case, (batch, M, N) if batch > 1 else (M, N), "f32", -3, 3)
+        if batch > 1:
+            want = np.stack([ops.gemm(A[b], B[b], dtype, transB=tb, alpha=alpha, beta=beta, C0=C0[b]) for b in range(batch)])
+        else:
+            want = ops.gemm(A, B, dtype, transB=tb, alpha=alpha, beta=beta, C0=C0)
+        got = run_gemm(gs, dtype, M, N, K, tb, None, A, B, alpha=alpha, beta=beta, C0=C0, batch=batch)
+        assert np.abs(want).max() < 2 ** 22
+        assert np.array_equal(got, want), f"case {case}: max abs diff {np.abs(got - want).max()}"
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_random_conv_geometries_with_constructed_schedules(gs, dtype):
+    """Seeded random convolution geometries (filter sizes 1-5, strides 1-3, paddings 0-2, channel counts with and
+    without whole vectors), each with the constructed schedule: bit-exact on integers."""
+    import torch
+    rng = np.random.default_rng(11407)
+    for case in range(16):
+        r, s = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        stride, pad = int(rng.integers(1, 4)), int(rng.integers(0, 3))
+        n, c, k = int(rng.integers(1, 4)), int(rng.integers(1, 5)) * (8 if case % 2 == 0 else 3), int(rng.integers(1, 90))
+        h, w = int(rng.integers(max(r - 2 * pad, 1), 24)), int(rng.integers(max(s - 2 * pad, 1), 24))
+        print(f"case {case}: {dtype} n={n} c={c} {h}x{w} k={k} {r}x{s} stride {stride} pad {pad}", flush=True)
+        I = inputs.small_ints(1000 + case, (n, c, h, w), dtype, -2, 2)
+        W = inputs.small_ints(1100 + case, (k, c, r, s), dtype, -2, 2)
+        want = ops.conv2d(I, W, dtype, stride=stride, pad=pad)
+        p = gs.conv_problem(dtype, n, c, h, w, k, r, s, stride, pad)
+        dO = gs.empty_device(want.shape)
+        dO.fill_(float("nan"))
+        gs.conv2d(p, gs.to_device(I, dtype), gs.to_device(W, dtype), dO, None, gs.conv_workspace(p))
+        torch.cuda.synchronize()
+        assert np.array_equal(gs.to_host_f64(dO), want), f"case {case}"
