@@ -64,7 +64,7 @@ class Case:
         t0 = time.perf_counter()
         self.sched = gs.construct(self.p, seed=0, opts=opts)
         self.construct_s = time.perf_counter() - t0
-        self.ws = None if self.is_gemm else gs.conv_workspace(self.p, self.sched)
+        self.ws = gs.gemm_workspace(self.p, self.sched) if self.is_gemm else gs.conv_workspace(self.p, self.sched)
         self.sets = [(self.a, self.b, self.out)]
         torch.cuda.synchronize()
 
@@ -74,9 +74,9 @@ class Case:
         if not self.is_gemm:
             gs.conv2d(self.p, a, b, out, self.sched, self.ws)
         elif w.batch > 1:
-            gs.bmm(self.p, a, b, out, 1.0, 0.0, self.sched)
+            gs.bmm(self.p, a, b, out, 1.0, 0.0, self.sched, workspace=self.ws)
         else:
-            gs.gemm(self.p, a, b, out, 1.0, 0.0, self.sched)
+            gs.gemm(self.p, a, b, out, 1.0, 0.0, self.sched, workspace=self.ws)
 
     def time_cold_ms(self, launches=20):
         """Average launch duration when every launch works on another copy of the operands, the
@@ -211,6 +211,27 @@ def variant_rows(gs, inputs, steps):
                          c.sched.tile[1][1], c.sched.stages, c.sched.direct_lds),
                      "parity_rel_frobenius_sampled": c.parity(256)})
         del c
+        torch.cuda.empty_cache()
+    return rows
+
+
+def deep_k_rows(gs, inputs):
+    """Contractions with few output tiles and a deep k: the constructed schedule (which splits k) beside the best
+    schedule without a split."""
+    import torch
+    rows = []
+    for i in range(len(inputs.DEEP_K_GEMMS)):
+        wl = inputs.deep_k_gemm(i)
+        c = Case(gs, inputs, wl)
+        m = c.time_median_ms(30, 5)
+        c1 = Case(gs, inputs, wl, opts=gs.ConstructOpts(0, 0, 0, 0, 0, 0, 1, 0))
+        m1 = c1.time_median_ms(10, 3)
+        rows.append({"workload": wl.name, "us": m * 1e3, "tflops": wl.flops / (m * 1e-3) / 1e12,
+                     "kernel_id": c.sched.kernel_id, "split_k": c.sched.split_k, "predicted_us": c.sched.predicted_us,
+                     "workspace_MB": gs.workspace_bytes(c.p, c.sched) / 1e6,
+                     "unsplit_us": m1 * 1e3, "unsplit_kernel_id": c1.sched.kernel_id,
+                     "parity_rel_frobenius_sampled": c.parity(128)})
+        del c, c1, wl
         torch.cuda.empty_cache()
     return rows
 
@@ -413,6 +434,7 @@ def main():
             del c, wl
             torch.cuda.empty_cache()
         line["unbalanced_gemms"] = nxt
+        line["deep_k_gemms"] = deep_k_rows(gs, inputs)
         line["variants"] = variant_rows(gs, inputs, steps2)
         line["operator_table"] = operator_table_rows(gs, inputs)
         line["ablation"] = ablation(gs, inputs)

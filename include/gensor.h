@@ -75,7 +75,7 @@ typedef struct {
   int32_t unroll;             /* MFMA k-steps unrolled per LDS stage = BK / (k per fragment) */
   int32_t vec_bytes;          /* width of one global access: 16, or the element size (scalar path) */
   int32_t direct_lds;         /* 1: global->LDS loads bypass registers */
-  int32_t split_k;            /* reserved, 1 */
+  int32_t split_k;            /* 1..16 workgroups per tile of the last, partly filled round (GEMM/BMM; see gensor_gemm) */
   int32_t wg_remap;           /* tile rows per panel in the workgroup->tile map (L2 reuse per XCD) */
   double predicted_us;        /* cost-model time of this schedule for the problem */
   double construct_s;         /* wall time gensor_construct spent */
@@ -121,6 +121,8 @@ typedef struct {
   int32_t keep_policy;        /* 0: keep every complete state; 1: the paper's printed keep probability */
   int32_t tiling_benefit;     /* 0: Eq. 1 as printed; 1: footprint ratio inverted (ablation) */
   int32_t no_vthread;         /* 1: setVThread disabled (ablation) */
+  int32_t no_split_k;         /* 1: only split_k = 1 is ranked (callers without a workspace) */
+  int32_t reserved;
 } gensor_construct_opts;
 
 /*
@@ -157,7 +159,23 @@ gensor_status gensor_instance_schedule(int32_t id, const gensor_problem* p, gens
  * A, B: in_dtype, C: out_dtype, row-major with leading dimensions lda, ldb, ldc in
  * elements (lda >= K or M if transA, ldb >= N or K if transB, ldc >= N).
  * s == NULL: a schedule is constructed for `p` (seed 0) and remembered per shape.
- * workspace is unused (pass NULL, 0).
+ *
+ * Split-k (s->split_k > 1).  Tiles are dealt to the compute units in rounds of
+ * gensor_hw_mi355x()->compute_units.  The tiles of the last round, if it is not full (every
+ * tile when there are fewer tiles than units), are each computed by split_k workgroups,
+ * every one over its own range of whole k tiles (needs ceil(K / BK) >= split_k, else
+ * NO_SCHEDULE); the parts of a tile leave fp32 partial tiles in `workspace` and the part
+ * that finishes last adds them up (two parts: one order of addition; more: in part order,
+ * so the result is reproducible) and writes C.  This is what a contraction with few output
+ * tiles and a deep k needs to occupy the chip.  `workspace` is device memory, 256-byte
+ * aligned, at least gensor_workspace_bytes(s, p) bytes (WORKSPACE otherwise): arrival
+ * counters, which the call clears itself with a small launch of its own in front of the
+ * operator, then the partial tiles.  It is scratch: nothing is kept in it between calls, and
+ * two calls that overlap in time must not share it.  If the tile count is a whole number of
+ * rounds nothing is split and no workspace is needed (gensor_workspace_bytes returns 0).
+ * With s == NULL split-k schedules are ranked only when a workspace is passed, and one too
+ * small for the ranking's choice selects the best unsplit schedule instead.
+ * Schedules with split_k == 1 use no workspace (pass NULL, 0).
  */
 gensor_status gensor_gemm(const gensor_schedule* s, const gensor_problem* p, float alpha,
                           const void* A, int64_t lda, const void* B, int64_t ldb,
@@ -194,6 +212,10 @@ gensor_status gensor_conv2d(const gensor_schedule* s, const gensor_problem* p,
                             const void* input, const void* weight, void* output,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Bytes of workspace the operator call on `p` with schedule `s` needs: the compacted input of a
+ * strided pointwise convolution, or the counters and partial tiles of a split-k GEMM/BMM
+ * (s required); 0 if none.  For a convolution s == NULL gives the most any schedule the
+ * library may construct can ask for. */
 size_t gensor_workspace_bytes(const gensor_schedule* s, const gensor_problem* p);
 
 /*

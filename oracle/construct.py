@@ -61,7 +61,7 @@ Readings (the paper is silent or garbled here)
 from __future__ import annotations
 
 import math
-from dataclasses import dataclass, field
+from dataclasses import dataclass, field, replace
 from typing import List, Optional, Sequence, Tuple
 
 M64 = (1 << 64) - 1
@@ -121,6 +121,7 @@ class Opts:
     keep_policy: int = 0
     tiling_benefit: int = 0
     no_vthread: int = 0
+    no_split_k: int = 0
 
 
 @dataclass
@@ -379,6 +380,8 @@ class Instance:
     vec: int
     stages: int
     direct: int
+    split_ok: int = 0      # also compiled with split tiles
+    split: int = 1         # split factor of a pick
 
 
 def predict_patch_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, stages) -> float:
@@ -433,11 +436,20 @@ def predict_patch_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, stages) -> floa
     return max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + hw.launch_us
 
 
-def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, direct) -> float:
+SPLITS = (1, 2, 3, 4, 6, 8, 12, 16)      # split factors the ranking tries on every candidate instance
+
+
+def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, direct, split=1) -> float:
     """Analytical time of one launch: per-CU pipeline limits (MFMA, LDS, L2 feed) scaled by
-    how many tiles the busiest CU owns, an epilogue that streams C, bounded below by HBM."""
+    how many tiles the busiest CU owns, an epilogue that streams C, bounded below by HBM.
+    split > 1: the tiles that do not fill a whole round of compute units (all of them when there are
+    fewer tiles than units) are computed by `split` workgroups each over 1/split of the k tiles; the
+    parts exchange fp32 partial tiles through device memory (a quarter of the HBM rate) and a dependent
+    launch clears their arrival counters first.  Infeasible if there is nothing to split."""
     if view.bsrc == 2 and direct and view.conv is not None:
-        return predict_patch_us(view, hw, bm, bn, bk, wm, wn, kg, stages)
+        return predict_patch_us(view, hw, bm, bn, bk, wm, wn, kg, stages) if split == 1 else -1.0
+    if split < 1 or (split > 1 and view.bsrc not in (0, 1)):
+        return -1.0
     e, eo = view.e, view.e_out
     g = 16 if e == 2 else 8
     mb = 32 if kg == g else 16
@@ -457,9 +469,18 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     occ = min(hw.lds_bytes_per_cu // lds, (hw.simds_per_cu * waves_per_simd) // nwaves, 8)
     if occ < 1:
         return -1.0
-    cu_tiles = math.ceil(tiles / hw.compute_units)
-    resident = min(occ, cu_tiles)
-    kp = math.ceil(view.K / bk) * bk
+    nk = float(math.ceil(view.K / bk))
+    whole, nk_part = float(tiles), nk
+    if split > 1:
+        whole = float(math.floor(tiles / hw.compute_units) * hw.compute_units)
+        if whole == tiles or nk < split:
+            return -1.0
+        nk_part = float(math.ceil(nk / split))
+    cu_whole = float(math.ceil(whole / hw.compute_units))
+    cu_part = float(math.ceil((tiles - whole) * split / hw.compute_units))
+    cu_tiles = cu_whole + cu_part
+    resident = min(float(occ), cu_tiles)
+    kp = nk * bk
     peak = (hw.mfma_tflops_16bit if e == 2 else hw.mfma_tflops_f32) * 1e6 / hw.compute_units   # flop/us per CU
     simd_use = min(1.0, nwaves * resident / hw.simds_per_cu)
     t_mfma = 2.0 * bm * bn * kp / (peak * simd_use * (1.0 if mb == 32 else 0.9))
@@ -477,25 +498,36 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
     # every k tile boundary (barrier, refill of the fragment pipeline) exposes a share of the memory latency
     # (a ring of three and more stages keeps more tiles in flight; measured to pay for k-contiguous operands)
     t_ktile = 0.25 * hw.latency_ns[0] * 1e-3
-    nk = float(math.ceil(view.K / bk))
-    t_sync = nk * t_ktile
-    if stages > 2 and view.bsrc == 0:
-        t_sync = t_sync / (stages - 1)
-    if stages == 1:
-        t_sync = t_sync + (nk - 1.0) * 4.0 * t_ktile       # a single buffer: each further tile waits out its own fetch
-    t_main = max(t_mfma, t_lds, t_feed) / overlap + t_sync
+
+    def sync_time(tiles_k: float) -> float:
+        t = tiles_k * t_ktile
+        if stages > 2 and view.bsrc == 0:
+            t = t / (stages - 1)
+        if stages == 1:
+            t = t + (tiles_k - 1.0) * 4.0 * t_ktile        # a single buffer: each further tile waits out its own fetch
+        return t
+
+    t_pipe = max(t_mfma, t_lds, t_feed)
+    t_part = t_pipe * (nk_part / nk) / overlap + sync_time(nk_part)       # one part of a split tile
+    t_main = t_pipe / overlap + sync_time(nk)
     hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units
     t_epi = bm * bn * eo / (0.8 * hbm_bw_cu)
     t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3
     # a second resident workgroup hides the stores of the first; further ones add nothing
-    t_cu = cu_tiles * (t_main + t_epi / min(resident, 2)) + t_fill
+    hide = min(resident, 2.0)
+    # a part writes its partial tile, and one part in `split` reads the others' and stores C
+    t_swap = bm * bn * 4.0 / (0.8 * hbm_bw_cu)
+    t_cu = cu_whole * (t_main + t_epi / hide) + cu_part * (t_part + t_swap + (t_swap * (split - 1) + t_epi) / split / hide) + t_fill
     bytes_total = view.batch * (e * (view.M * view.K + view.K * view.N) + eo * view.M * view.N)
-    t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3)
+    bytes_swap = (tiles - whole) * (2.0 * split - 1.0) * bm * bn * 4.0 if split > 1 else 0.0
+    t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3) + bytes_swap / (0.25 * hw.bandwidth_gbs[0] * 1e3)
     # soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)
-    return max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + hw.launch_us * (3.5 if view.prepass else 1.0)
+    return (max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + hw.launch_us * (3.5 if view.prepass else 1.0)
+            + (hw.launch_us if split > 1 else 0.0))
 
 
-def pick(view: View, hw: Hw, kept: Sequence[State], instances: Sequence[Instance], vec_ok: bool) -> Tuple[Optional[Instance], float, int]:
+def pick(view: View, hw: Hw, kept: Sequence[State], instances: Sequence[Instance], vec_ok: bool,
+         no_split_k: int = 0) -> Tuple[Optional[Instance], float, int]:
     """Rank kept complete states by the cost model; return the best compiled instance."""
     best, best_us, scored = None, 0.0, 0
     seen = set()
@@ -515,9 +547,12 @@ def pick(view: View, hw: Hw, kept: Sequence[State], instances: Sequence[Instance
                 continue
             if i.direct and view.bsrc != 2 and view.K % i.bk != 0:
                 continue
-            us = predict_us(view, hw, i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn, i.vec, i.stages, i.direct)
-            if us > 0 and (best is None or us < best_us):
-                best, best_us = i, us
+            for split in SPLITS:
+                if split > 1 and (no_split_k or not i.split_ok):
+                    break
+                us = predict_us(view, hw, i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn, i.vec, i.stages, i.direct, split)
+                if us > 0 and (best is None or us < best_us):
+                    best, best_us = replace(i, split=split), us
         us0 = predict_us(view, hw, bm, bn, bk, wm, wn, kg, s.v[0], s.v[1], 1 if vec_ok else 0, 2, 0)
         if us0 > 0:
             ranked.append((us0, s))
@@ -542,7 +577,7 @@ def construct(view: View, hw: Hw, opts: Opts, seed: int, instances: Sequence[Ins
     kept: List[State] = []
     for chain in range(opts.chains):
         kept.extend(walk(view, hw, opts, seed, chain).kept)
-    return pick(view, hw, kept, instances, vec_ok)
+    return pick(view, hw, kept, instances, vec_ok, opts.no_split_k)
 
 
 def transition_row(view: View, hw: Hw, opts: Opts, s: State, T_level: float) -> List[float]:

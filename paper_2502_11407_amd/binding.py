@@ -64,7 +64,8 @@ class Hw(C.Structure):
 
 class ConstructOpts(C.Structure):
     _fields_ = [("T0", C.c_double), ("threshold", C.c_double), ("chains", C.c_int32),
-                ("keep_policy", C.c_int32), ("tiling_benefit", C.c_int32), ("no_vthread", C.c_int32)]
+                ("keep_policy", C.c_int32), ("tiling_benefit", C.c_int32), ("no_vthread", C.c_int32),
+                ("no_split_k", C.c_int32), ("reserved", C.c_int32)]
 
 
 class GensorError(RuntimeError):
@@ -196,21 +197,30 @@ def _sref(s):
     return C.byref(s) if s is not None else None
 
 
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
 def gemm(p: Problem, A, B, Cout, alpha: float = 1.0, beta: float = 0.0, schedule: Optional[Schedule] = None,
-         lda: Optional[int] = None, ldb: Optional[int] = None, ldc: Optional[int] = None, stream=None):
-    """C = alpha op(A) op(B) + beta C on device tensors (2-D, row-major with unit inner stride)."""
+         lda: Optional[int] = None, ldb: Optional[int] = None, ldc: Optional[int] = None, stream=None, workspace=None):
+    """C = alpha op(A) op(B) + beta C on device tensors (2-D, row-major with unit inner stride).
+    `workspace`: device tensor of at least workspace_bytes(p, schedule) bytes for a split-k schedule (or None)."""
+    ws_ptr, ws_len = _ws(workspace)
     st = lib.gensor_gemm(_sref(schedule), C.byref(p), alpha, A.data_ptr(), lda if lda is not None else A.stride(0),
                          B.data_ptr(), ldb if ldb is not None else B.stride(0), beta,
-                         Cout.data_ptr(), ldc if ldc is not None else Cout.stride(0), None, 0, _stream_ptr(stream))
+                         Cout.data_ptr(), ldc if ldc is not None else Cout.stride(0), ws_ptr, ws_len, _stream_ptr(stream))
     _check(st, "gensor_gemm")
 
 
 def bmm(p: Problem, A, B, Cout, alpha: float = 1.0, beta: float = 0.0, schedule: Optional[Schedule] = None,
-        stream=None):
+        stream=None, workspace=None):
     """Batched: 3-D device tensors [batch][rows][cols]."""
+    ws_ptr, ws_len = _ws(workspace)
     st = lib.gensor_bmm(_sref(schedule), C.byref(p), alpha, A.data_ptr(), A.stride(1), A.stride(0),
                         B.data_ptr(), B.stride(1), B.stride(0), beta,
-                        Cout.data_ptr(), Cout.stride(1), Cout.stride(0), None, 0, _stream_ptr(stream))
+                        Cout.data_ptr(), Cout.stride(1), Cout.stride(0), ws_ptr, ws_len, _stream_ptr(stream))
     _check(st, "gensor_bmm")
 
 
@@ -257,6 +267,13 @@ def mfma_probe(dtype: str, operands, sink, iters: int, stream=None):
     values are the A and B fragments, `sink` a device tensor of 65536 floats."""
     st = lib.gensor_mfma_probe(DTYPE[dtype], operands.data_ptr(), sink.data_ptr(), iters, _stream_ptr(stream))
     _check(st, "gensor_mfma_probe")
+
+
+def gemm_workspace(p: Problem, schedule: Schedule):
+    """Device buffer for gensor_gemm / gensor_bmm on `p` with a split-k `schedule`, or None if it needs none (plumbing)."""
+    import torch
+    n = workspace_bytes(p, schedule)
+    return torch.empty(n, dtype=torch.uint8, device="cuda") if n else None
 
 
 def conv_workspace(p: Problem, schedule: Optional[Schedule] = None):

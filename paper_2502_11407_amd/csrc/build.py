@@ -43,6 +43,9 @@ def generate():
             src.append("typedef %s C_%d;" % (lattice.cfg_type(d), d["id"]))
             src.append("hipError_t launch_%d(const KernelArgs& a, hipStream_t st) { return %s<C_%d>(a, st); }"
                        % (d["id"], "launch_conv_instance" if d["units"] else "launch_instance", d["id"]))
+            if lattice.splittable(d):
+                src.append("hipError_t launch_split_%d(const KernelArgs& a, hipStream_t st) { return launch_instance<C_%d, true>(a, st); }"
+                           % (d["id"], d["id"]))
         src.append("}  // namespace gensor\n")
         path = os.path.join(GEN, "%s_%03d.hip" % ("conv" if group[0]["units"] else "inst", t // PER_TU))
         _write_if_changed(path, "\n".join(src))
@@ -55,6 +58,8 @@ def generate():
     reg = ['#include "registry.hpp"', "#if !defined(__HIP_DEVICE_COMPILE__)", "namespace gensor {"]
     for d in L:
         reg.append("hipError_t launch_%d(const KernelArgs&, hipStream_t);" % d["id"])
+        if lattice.splittable(d):
+            reg.append("hipError_t launch_split_%d(const KernelArgs&, hipStream_t);" % d["id"])
     reg.append("const InstanceDesc g_instances[] = {")
     for d in L:
         es = 4 if d["dt"] == "f32" else 2
@@ -63,9 +68,10 @@ def generate():
         b_bytes = d["bn"] * d["bk"] * es if (d["bsrc"] == "KC" or d["direct"]) else d["bk"] * (d["bn"] * es + 32)
         lds = 0 if d["units"] else (a_bytes + b_bytes) * d["stages"]
         threads = (d["bm"] // d["wm"]) * (d["bn"] // d["wn"]) * 64
-        reg.append("  {%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, launch_%d}," % (
+        reg.append("  {%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, launch_%d, %s}," % (
             d["id"], lattice.DT[d["dt"]], lattice.DT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"],
-            d["vm"], d["vn"], lattice.BSRC[d["bsrc"]], d["vec"], d["stages"], d["direct"], lds, threads, kg, d["units"], d["id"]))
+            d["vm"], d["vn"], lattice.BSRC[d["bsrc"]], d["vec"], d["stages"], d["direct"], lds, threads, kg, d["units"], d["id"],
+            ("launch_split_%d" % d["id"]) if lattice.splittable(d) else "nullptr"))
     reg.append("};")
     reg.append("const int g_num_instances = %d;" % len(L))
     reg.append("}  // namespace gensor")

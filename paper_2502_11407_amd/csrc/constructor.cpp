@@ -78,7 +78,7 @@ int next_pow2(int64_t x) {
 void make_ctx(const GemmView& v, const gensor_hw* hw, const gensor_construct_opts* o, Ctx* c) {
   c->view = v;
   c->hw = hw ? *hw : kMi355x;
-  gensor_construct_opts d = {std::ldexp(1.0, 30), std::ldexp(1.0, -70), 1024, 0, 0, 0};
+  gensor_construct_opts d = {std::ldexp(1.0, 30), std::ldexp(1.0, -70), 1024, 0, 0, 0, 0, 0};
   if (o) {
     if (o->T0 > 0) d.T0 = o->T0;
     if (o->threshold > 0) d.threshold = o->threshold;
@@ -86,6 +86,7 @@ void make_ctx(const GemmView& v, const gensor_hw* hw, const gensor_construct_opt
     d.keep_policy = o->keep_policy;
     d.tiling_benefit = o->tiling_benefit;
     d.no_vthread = o->no_vthread;
+    d.no_split_k = o->no_split_k;
   }
   c->opts = d;
   c->g = v.esize == 2 ? 16 : 8;
@@ -314,10 +315,15 @@ double predict_patch(const GemmView& v, const gensor_hw& hw, int bm, int bn, int
   return (t_cu > t_hbm ? t_cu : t_hbm) + 0.3 * (t_cu > t_hbm ? t_hbm : t_cu) + hw.launch_us;
 }
 
+// split > 1: the tiles that do not fill a whole round of compute units (all of them when there are fewer tiles
+// than units) are computed by `split` workgroups each, every one over 1/split of the k tiles; the parts of a
+// tile exchange fp32 partial tiles through device memory (measured: about a quarter of the HBM rate) and a
+// dependent launch clears their arrival counters first.  Infeasible if there is nothing to split.
 double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, int wm, int wn, int kg,
-               int vm, int vn, int vec, int stages, int direct) {
+               int vm, int vn, int vec, int stages, int direct, int split) {
   (void)vm; (void)vn;
-  if (v.bsrc == B_CONV && direct) return predict_patch(v, hw, bm, bn, bk, wm, wn, kg, stages);
+  if (v.bsrc == B_CONV && direct) return split == 1 ? predict_patch(v, hw, bm, bn, bk, wm, wn, kg, stages) : -1.0;
+  if (split < 1 || (split > 1 && v.bsrc != B_KC && v.bsrc != B_NC)) return -1.0;
   const int e = v.esize, eo = v.osize;
   const int g = e == 2 ? 16 : 8;
   const int mb = kg == g ? 32 : 16;
@@ -335,9 +341,18 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   if ((hw.simds_per_cu * waves_per_simd) / nwaves < occ) occ = (hw.simds_per_cu * waves_per_simd) / nwaves;
   if (occ > 8) occ = 8;
   if (occ < 1) return -1.0;
-  const double cu_tiles = std::ceil(tiles / hw.compute_units);
+  const double nk = std::ceil((double)v.K / bk);
+  double whole = tiles, nk_part = nk;
+  if (split > 1) {
+    whole = std::floor(tiles / hw.compute_units) * hw.compute_units;
+    if (whole == tiles || nk < split) return -1.0;
+    nk_part = std::ceil(nk / split);
+  }
+  const double cu_whole = std::ceil(whole / hw.compute_units);
+  const double cu_part = std::ceil((tiles - whole) * split / hw.compute_units);
+  const double cu_tiles = cu_whole + cu_part;
   const double resident = occ < cu_tiles ? occ : cu_tiles;
-  const double kp = std::ceil((double)v.K / bk) * bk;
+  const double kp = nk * bk;
   const double peak = (e == 2 ? hw.mfma_tflops_16bit : hw.mfma_tflops_f32) * 1e6 / hw.compute_units;
   double simd_use = nwaves * resident / hw.simds_per_cu;
   if (simd_use > 1.0) simd_use = 1.0;
@@ -359,26 +374,38 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   // every k tile boundary (barrier, refill of the fragment pipeline) exposes a share of the memory latency
   // (a ring of three and more stages keeps more tiles in flight; measured to pay for k-contiguous operands)
   const double t_ktile = 0.25 * hw.latency_ns[0] * 1e-3;
-  const double nk = std::ceil((double)v.K / bk);
-  double t_sync = nk * t_ktile;
-  if (stages > 2 && v.bsrc == B_KC) t_sync = t_sync / (stages - 1);
-  if (stages == 1) t_sync = t_sync + (nk - 1.0) * 4.0 * t_ktile;       // a single buffer: each further tile waits out its own fetch
-  t_main = t_main / overlap + t_sync;
+  auto sync_time = [&](double tiles_k) {
+    double t = tiles_k * t_ktile;
+    if (stages > 2 && v.bsrc == B_KC) t = t / (stages - 1);
+    if (stages == 1) t = t + (tiles_k - 1.0) * 4.0 * t_ktile;          // a single buffer: each further tile waits out its own fetch
+    return t;
+  };
+  const double t_part = t_main * (nk_part / nk) / overlap + sync_time(nk_part);     // one part of a split tile
+  t_main = t_main / overlap + sync_time(nk);
   const double hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units;
   const double t_epi = bm * bn * eo / (0.8 * hbm_bw_cu);
   const double t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3;
   // a second resident workgroup hides the stores of the first; further ones add nothing
-  const double t_cu = cu_tiles * (t_main + t_epi / (resident < 2.0 ? resident : 2.0)) + t_fill;
+  const double hide = resident < 2.0 ? resident : 2.0;
+  // a part writes its partial tile, and one part in `split` reads the others' and stores C
+  const double t_swap = bm * bn * 4.0 / (0.8 * hbm_bw_cu);
+  const double t_cu = cu_whole * (t_main + t_epi / hide) + cu_part * (t_part + t_swap + (t_swap * (split - 1) + t_epi) / split / hide) + t_fill;
   const double bytes_total = (double)v.batch * ((double)e * ((double)v.M * v.K + (double)v.K * v.N) + (double)eo * v.M * v.N);
-  const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3);
+  const double bytes_swap = split > 1 ? (tiles - whole) * (2.0 * split - 1.0) * bm * bn * 4.0 : 0.0;
+  const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3) + bytes_swap / (0.25 * hw.bandwidth_gbs[0] * 1e3);
   // soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)
   const bool prepass = v.pointwise && v.cstride > 1 && v.bsrc != B_NCS2;   // the input is compacted by a dependent launch of its own
-  return (t_cu > t_hbm ? t_cu : t_hbm) + 0.3 * (t_cu > t_hbm ? t_hbm : t_cu) + hw.launch_us * (prepass ? 3.5 : 1.0);
+  return (t_cu > t_hbm ? t_cu : t_hbm) + 0.3 * (t_cu > t_hbm ? t_hbm : t_cu) + hw.launch_us * (prepass ? 3.5 : 1.0) +
+         (split > 1 ? hw.launch_us : 0.0);
 }
 
-double predict_instance(const GemmView& v, const gensor_hw& hw, const InstanceDesc& d) {
-  return predict(v, hw, d.bm, d.bn, d.bk, d.wm, d.wn, d.kg, d.vm, d.vn, d.vec, d.stages, d.direct);
+double predict_instance(const GemmView& v, const gensor_hw& hw, const InstanceDesc& d, int split = 1) {
+  if (split > 1 && !d.launch_split) return -1.0;
+  return predict(v, hw, d.bm, d.bn, d.bk, d.wm, d.wn, d.kg, d.vm, d.vn, d.vec, d.stages, d.direct, split);
 }
+
+// split factors the ranking tries on every candidate instance
+const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16};
 
 bool usable(const InstanceDesc& d, const GemmView& v, bool vec_ok) {
   if (!instance_serves(d, v)) return false;
@@ -409,6 +436,7 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
   std::set<Etir> seen;
   const InstanceDesc* best = nullptr;
   double best_us = 0.0;
+  int best_split = 1;
   int scored = 0;
   const Etir* best_state = nullptr;
   double best_state_us = 0.0;
@@ -421,11 +449,14 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
       const InstanceDesc& d = g_instances[i];
       if (d.bm != e.tile[0][0] || d.bn != e.tile[1][0] || d.wm != e.tile[0][1] || d.wn != e.tile[1][1]) continue;
       if (!usable(d, v, vec_ok)) continue;
-      const double us = predict_instance(v, c.hw, d);
-      if (us > 0 && (!best || us < best_us)) { best = &d; best_us = us; }
+      for (int split : kSplits) {
+        if (split > 1 && c.opts.no_split_k) break;
+        const double us = predict_instance(v, c.hw, d, split);
+        if (us > 0 && (!best || us < best_us)) { best = &d; best_us = us; best_split = split; }
+      }
     }
     const double us0 = predict(v, c.hw, e.tile[0][0], e.tile[1][0], e.tile[2][0], e.tile[0][1], e.tile[1][1], e.tile[2][1],
-                               e.v[0], e.v[1], vec_ok ? 1 : 0, 2, 0);
+                               e.v[0], e.v[1], vec_ok ? 1 : 0, 2, 0, 1);
     if (us0 > 0 && (!best_state || us0 < best_state_us)) { best_state = &e; best_state_us = us0; }
   }
   if (!best && best_state) {
@@ -446,6 +477,7 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
   }
   if (!best) return GENSOR_ERR_NO_SCHEDULE;
   schedule_from_instance(*best, out);
+  out->split_k = best_split;
   out->predicted_us = best_us;
   out->iterations = max_steps;
   out->chains = c.opts.chains;
@@ -495,5 +527,5 @@ extern "C" double gensor_predict_us(const gensor_schedule* s, const gensor_probl
   if (gemm_view(p, &v) != GENSOR_OK) return -1.0;
   const gensor_hw& h = hw ? *hw : kMi355x;
   return predict(v, h, s->tile[0][0], s->tile[1][0], s->tile[2][0], s->tile[0][1], s->tile[1][1], s->tile[2][1],
-                 s->vthread[0], s->vthread[1], s->vec_bytes == 16 ? 1 : 0, s->stages, s->direct_lds);
+                 s->vthread[0], s->vthread[1], s->vec_bytes == 16 ? 1 : 0, s->stages, s->direct_lds, s->split_k);
 }

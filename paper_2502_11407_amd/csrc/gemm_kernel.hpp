@@ -50,6 +50,11 @@ struct KernelArgs {
   float alpha, beta;
   int32_t tiles_m, tiles_n, batch;
   int32_t panel;                   // tile rows per panel in the workgroup->tile map
+  // split-k: workgroups [0, whole) compute one whole tile each; the tiles behind them are computed by
+  // `split` workgroups each, every one over its own range of k tiles (split == 1: whole == all tiles)
+  int32_t split, whole;
+  float* partials;                 // [tile - whole][split][BM * BN] fp32, lane-major inside a slot
+  uint32_t* counters;              // [tile - whole][waves per workgroup], zero at launch
   // convolution geometry (B_CONV only)
   int32_t cC, cH, cW, cR, cS, cP, cQ, cStride, cPad;
   // patch-staged convolution only: images, LDS plan and tensor sizes in bytes (each < 2^31)
@@ -199,7 +204,9 @@ __device__ inline int swizzled_chunk(int row, int chunk, int rpp, int cpr) { ret
 __device__ inline int nc_swizzle(int krow) { return ((krow & 3) << 6) ^ (((krow >> 3) & 1) << 5); }
 
 // ---------------------------------------------------------------- the kernel
-template <typename C>
+// SPLIT: the launch has split tiles (KernelArgs::split > 1); without it the kernel knows at compile time
+// that every workgroup owns a whole tile.
+template <typename C, bool SPLIT = false>
 __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArgs args) {
   typedef typename C::T T;
   typedef Mfma<T, C::MB> MF;
@@ -221,7 +228,20 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   const int tiles_per_batch = args.tiles_m * args.tiles_n;
   const int total = tiles_per_batch * args.batch;
   int wg = blockIdx.x;
-  if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
+  int part = 0, parts = 1;
+  if constexpr (!SPLIT) {
+    if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
+  } else if (wg < args.whole) {
+    if ((args.whole & 7) == 0) wg = (wg & 7) * (args.whole >> 3) + (wg >> 3);
+  } else {
+    // the split tiles come last in launch order; the `split` workgroups of one tile are neighbours on one XCD
+    parts = args.split;
+    int u = wg - args.whole;
+    const int units = (total - args.whole) * parts;
+    if ((units & 7) == 0) u = (u & 7) * (units >> 3) + (u >> 3);
+    wg = args.whole + u / parts;
+    part = u - (wg - args.whole) * parts;
+  }
   const int bidx = wg / tiles_per_batch;
   int t = wg - bidx * tiles_per_batch;
   int tile_m, tile_n;
@@ -237,8 +257,19 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   const int m0 = tile_m * BM;
   const int n0 = tile_n * BN;
 
-  const char* Ab = (const char*)args.A + (int64_t)bidx * args.strideA * ES;
-  const char* Bb = (const char*)args.B + (int64_t)bidx * args.strideB * ES;
+  // k range of this workgroup: the whole of K, or k tiles [part * nk / parts, (part + 1) * nk / parts) of a split
+  // tile.  The operand bases move to the first k of the range and Kx is its length, so everything below
+  // sees a shorter contraction.
+  int Kx = args.K;
+  int64_t k_first = 0;
+  if (SPLIT && parts > 1) {
+    const int nk_all = (args.K + BK - 1) / BK;
+    const int kt0 = part * nk_all / parts, kt1 = (part + 1) * nk_all / parts;
+    k_first = (int64_t)kt0 * BK;
+    Kx = min(args.K, kt1 * BK) - kt0 * BK;
+  }
+  const char* Ab = (const char*)args.A + ((int64_t)bidx * args.strideA + k_first) * ES;
+  const char* Bb = (const char*)args.B + ((int64_t)bidx * args.strideB + (C::BSRC == B_KC ? k_first : k_first * args.ldb)) * ES;
 
   // ---- accumulators
   Acc acc[C::MBLK][C::NBLK];
@@ -265,18 +296,18 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   const char* b_tile = (C::BSRC == B_KC) ? Bb + (int64_t)n0 * args.ldb * ES : (C::BSRC == B_NCS2 ? Bb : Bb + (int64_t)n0 * ES);
   auto rsrc_a = [&](int k0) {
     return __builtin_amdgcn_make_buffer_rsrc((void*)(a_tile + (int64_t)k0 * ES), 0,
-        clamp_records(((int64_t)(rows_valid - 1) * args.lda + (args.K - k0)) * ES), RSRC_FLAGS);
+        clamp_records(((int64_t)(rows_valid - 1) * args.lda + (Kx - k0)) * ES), RSRC_FLAGS);
   };
   auto rsrc_b = [&](int k0) {
     if constexpr (C::BSRC == B_KC)
       return __builtin_amdgcn_make_buffer_rsrc((void*)(b_tile + (int64_t)k0 * ES), 0,
-          clamp_records(((int64_t)(cols_valid - 1) * args.ldb + (args.K - k0)) * ES), RSRC_FLAGS);
+          clamp_records(((int64_t)(cols_valid - 1) * args.ldb + (Kx - k0)) * ES), RSRC_FLAGS);
     else if constexpr (C::BSRC == B_NCS2)
       return __builtin_amdgcn_make_buffer_rsrc((void*)(b_tile + (int64_t)k0 * args.ldb * ES), 0,
-          clamp_records((int64_t)(args.K - k0) * args.ldb * ES), RSRC_FLAGS);
+          clamp_records((int64_t)(Kx - k0) * args.ldb * ES), RSRC_FLAGS);
     else
       return __builtin_amdgcn_make_buffer_rsrc((void*)(b_tile + (int64_t)k0 * args.ldb * ES), 0,
-          clamp_records(((int64_t)(args.K - k0 - 1) * args.ldb + (args.N - n0)) * ES), RSRC_FLAGS);
+          clamp_records(((int64_t)(Kx - k0 - 1) * args.ldb + (args.N - n0)) * ES), RSRC_FLAGS);
   };
 
   // ---- who loads what.  A thread owns LDS chunk slots q = tid + i*THREADS of a
@@ -329,7 +360,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 
   // element-wise access for the scalar path and the convolution gather
   auto a_elem_bits = [&](int row, int k) -> uint32_t {
-    if (row < args.M && k < args.K) {
+    if (row < args.M && k < Kx) {
       int64_t idx = (int64_t)row * args.lda + k;
       if constexpr (ES == 4) return ((const uint32_t*)Ab)[idx];
       else return ((const uint16_t*)Ab)[idx];
@@ -337,7 +368,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     return 0u;
   };
   auto b_elem_bits = [&](int k, int col) -> uint32_t {
-    if (col >= args.N || k >= args.K) return 0u;
+    if (col >= args.N || k >= Kx) return 0u;
     int64_t idx;
     if constexpr (C::BSRC == B_KC) idx = (int64_t)col * args.ldb + k;
     else if constexpr (C::BSRC == B_NC) idx = (int64_t)k * args.ldb + col;
@@ -369,7 +400,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   // In a k-contiguous row a chunk beyond K would alias the next row, so those lanes are
   // sent out of range; this can only happen in the last k tile.
   auto fetch_a = [&](int k0, int st, int part = 0, int parts = 1) {
-    const bool full = args.K - k0 >= BK;
+    const bool full = Kx - k0 >= BK;
     if constexpr (SCALAR_A) {
 #pragma unroll
       for (int i = 0; i < C::A_LOADS; ++i) {
@@ -385,7 +416,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         if (C::A_CHUNKS % C::THREADS != 0 && tid + i * C::THREADS >= C::A_CHUNKS) break;
         if (i * parts < part * C::A_LOADS || i * parts >= (part + 1) * C::A_LOADS) continue;
         // (direct staging is only launched for K a multiple of BK: every tile is full)
-        const uint32_t off = (C::DIRECT || full || (int)a_kch[i] < args.K - k0) ? a_voff[i] : OOB;
+        const uint32_t off = (C::DIRECT || full || (int)a_kch[i] < Kx - k0) ? a_voff[i] : OOB;
         if constexpr (C::DIRECT)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (GENSOR_LDS void*)(lds + st * C::STAGE_BYTES + (i * C::THREADS + wave * 64) * 16),
                                                    16, off, 0, 0, 0);
@@ -395,7 +426,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     }
   };
   auto fetch_b = [&](int k0, int st, int part = 0, int parts = 1) {
-    const bool full = args.K - k0 >= BK;
+    const bool full = Kx - k0 >= BK;
     if constexpr (SCALAR_B) {
 #pragma unroll
       for (int i = 0; i < C::B_LOADS; ++i) {
@@ -417,7 +448,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         if (C::B_CHUNKS % C::THREADS != 0 && tid + i * C::THREADS >= C::B_CHUNKS) break;
         if (i * parts < part * C::B_LOADS || i * parts >= (part + 1) * C::B_LOADS) continue;
         uint32_t off = b_voff[i];
-        if constexpr (C::BSRC == B_KC && !C::DIRECT) off = (full || (int)b_kch[i] < args.K - k0) ? off : OOB;
+        if constexpr (C::BSRC == B_KC && !C::DIRECT) off = (full || (int)b_kch[i] < Kx - k0) ? off : OOB;
         if constexpr (C::DIRECT) {
           __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (GENSOR_LDS void*)(lds + st * C::STAGE_BYTES + C::A_BYTES + (i * C::THREADS + wave * 64) * 16),
                                                    16, off, 0, 0, 0);
@@ -592,7 +623,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   // ---- main loop over k tiles.  Tile kt+1 is fetched while tile kt is multiplied; its
   // first fragments are read right after the barrier, under the MFMAs of the last k step
   // of tile kt, so that the barrier and the LDS latency are covered by matrix work.
-  const int nk = (args.K + BK - 1) / BK;
+  const int nk = (Kx + BK - 1) / BK;
   constexpr bool PIPE = (C::KSTEPS % 2 == 0) && C::STAGES == 2;
   if constexpr (C::STAGES <= 2) {
     fetch_a(0, 0);
@@ -775,6 +806,61 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   // ones for 16x16 blocks).  Accumulating the transposed block instead, for 16-byte vector stores
   // of four columns per lane, measured slower everywhere (32 rows x 32 bytes per instruction:
   // -3 % on the 4096^3 GEMM, -9 % on 8192x3072x768, -11 % on the store-bound K = 64 shapes).
+  if (SPLIT && parts > 1) {
+    // Split tile: every wave leaves its accumulators in this workgroup's slot (16 bytes per lane and store,
+    // a wave's store one contiguous KiB) and counts itself in.  The wave that finds the other parts-1 already
+    // counted adds their slots to its own registers and goes on to the epilogue; the others are done.  Nothing
+    // waits.  Two parts: own registers plus the other slot (the sum of two terms has one order).  More: the
+    // slots are summed from memory in part order, so the result does not depend on who came last.
+    constexpr int NV = C::MBLK * C::NBLK * MF::NACC / 4;       // 16-byte groups per lane
+    constexpr int SLOT_BYTES = BM * BN * 4;
+    constexpr int DEVICE_SCOPE = 16;                           // sc1: the access is coherent across the whole device
+    const int64_t tile_slot = (int64_t)(wg - args.whole) * parts;
+    auto slot = [&](int o) {
+      return __builtin_amdgcn_make_buffer_rsrc((void*)((char*)args.partials + (tile_slot + o) * (int64_t)SLOT_BYTES), 0,
+                                               (uint32_t)SLOT_BYTES, RSRC_FLAGS);
+    };
+    const __amdgpu_buffer_rsrc_t own = slot(part);
+#pragma unroll
+    for (int g = 0; g < NV; ++g) {
+      const int b = g / (MF::NACC / 4), q = g % (MF::NACC / 4);
+      u32x4 v;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) v[x] = __builtin_bit_cast(uint32_t, (float)acc[b / C::NBLK][b % C::NBLK][4 * q + x]);
+      __builtin_amdgcn_raw_buffer_store_b128(v, own, (uint32_t)((g * C::THREADS + tid) * 16), 0, DEVICE_SCOPE);
+      if (g % 8 == 7) __builtin_amdgcn_sched_barrier(0);
+    }
+    // the slot's stores have completed (they write through to device scope) before the count
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_sched_barrier(0);
+    uint32_t before = 0;
+    if (lane == 0) before = atomicAdd(args.counters + (int64_t)(wg - args.whole) * C::WAVES + wave, 1u);
+    before = __builtin_amdgcn_readfirstlane(before);
+    if (before != (uint32_t)(parts - 1)) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    const bool from_memory = parts > 2;
+    if (from_memory) {
+#pragma unroll
+      for (int i = 0; i < C::MBLK; ++i)
+#pragma unroll
+        for (int j = 0; j < C::NBLK; ++j)
+#pragma unroll
+          for (int v = 0; v < MF::NACC; ++v) acc[i][j][v] = 0.f;
+    }
+    for (int o = 0; o < parts; ++o) {
+      if (!from_memory && o == part) continue;
+      const __amdgpu_buffer_rsrc_t src = slot(o);
+#pragma unroll
+      for (int g = 0; g < NV; ++g) {
+        const int b = g / (MF::NACC / 4), q = g % (MF::NACC / 4);
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(src, (uint32_t)((g * C::THREADS + tid) * 16), 0, DEVICE_SCOPE);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) acc[b / C::NBLK][b % C::NBLK][4 * q + x] += as_f32(v[x]);
+        if (g % 8 == 7) __builtin_amdgcn_sched_barrier(0);     // eight loads in flight, not all of them: registers
+      }
+    }
+  }
   typedef typename C::OutT OutT;
   constexpr int OS = ElemSize<OutT>::value;
   char* Cb = (char*)args.C + (int64_t)bidx * args.strideC * OS;

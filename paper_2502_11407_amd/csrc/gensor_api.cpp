@@ -181,12 +181,46 @@ namespace gensor {
 static size_t pointwise_workspace(const GemmView& v) {
   return v.pointwise && v.cstride > 1 && v.bsrc != B_NCS2 ? (size_t)(v.batch * v.K * v.N * v.esize) : 0;
 }
+
+// Split-k plan of instance d on view v with split factor `split`: the tiles that do not fill a whole
+// round of compute units (all of them when there are fewer tiles than units) are computed by `split`
+// workgroups each.  whole = tiles left unsplit; a plan with whole == tiles splits nothing.
+SplitPlan split_plan(const InstanceDesc& d, const GemmView& v, int split) {
+  SplitPlan pl;
+  const int64_t tiles = ((v.M + d.bm - 1) / d.bm) * ((v.N + d.bn - 1) / d.bn) * v.batch;
+  const int64_t cus = gensor_hw_mi355x()->compute_units;
+  pl.whole = split > 1 ? tiles / cus * cus : tiles;
+  pl.split = pl.whole == tiles ? 1 : split;
+  const int64_t waves = d.threads / 64;
+  pl.counter_bytes = pl.split > 1 ? ((tiles - pl.whole) * waves * 4 + 255) / 256 * 256 : 0;
+  pl.bytes = pl.split > 1 ? (size_t)(pl.counter_bytes + (tiles - pl.whole) * pl.split * (int64_t)d.bm * d.bn * 4) : 0;
+  return pl;
+}
+
+// Can the instance run a split tile?  It was compiled with the split path (operands fetched plainly, no
+// gather, no sampling) and every part gets at least one k tile.
+bool split_allowed(const InstanceDesc& d, const GemmView& v, int split) {
+  if (split == 1) return true;
+  if (split < 1 || split > 16 || !d.launch_split || (v.bsrc != B_KC && v.bsrc != B_NC)) return false;
+  return (v.K + d.bk - 1) / d.bk >= split;
+}
+
+__global__ void clear_counters(uint32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
 }  // namespace gensor
 
 // Only a strided pointwise convolution run as a batched GEMM through the compaction pre-pass
 // needs a workspace (the compacted copy of its input).
 extern "C" size_t gensor_workspace_bytes(const gensor_schedule* s, const gensor_problem* p) {
   GemmView v, w;
+  if (p && s && (p->op == GENSOR_OP_GEMM || p->op == GENSOR_OP_BMM)) {
+    // a split-k schedule: one counter per wave of every split tile, then one fp32 tile per part
+    if (s->split_k <= 1 || gemm_view(p, &v) != GENSOR_OK) return 0;
+    const InstanceDesc* d = find_instance(s, v);
+    return d && split_allowed(*d, v, s->split_k) ? split_plan(*d, v, s->split_k).bytes : 0;
+  }
   if (!p || p->op != GENSOR_OP_CONV2D || gemm_view(p, &v) != GENSOR_OK || gemm_view(p, &w, VIEW_PREPASS) != GENSOR_OK) return 0;
   const size_t need_pw = pointwise_workspace(w);
   if (!s) return need_pw;                    // what any schedule the library may construct can ask for
@@ -202,9 +236,9 @@ namespace {
 std::mutex g_memo_mutex;
 std::map<std::tuple<int, int, int, int, int, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int>, gensor_schedule> g_memo;
 
-gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, int view_mode, gensor_schedule* out) {
+gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, int view_mode, bool no_split, gensor_schedule* out) {
   auto key = std::make_tuple((int)p->op, (int)p->in_dtype, (int)p->out_dtype, (int)p->transB,
-                             (vec_ok ? 1 : 0) + 4 * view_mode,
+                             (vec_ok ? 1 : 0) + (no_split ? 2 : 0) + 4 * view_mode,
                              p->op == GENSOR_OP_CONV2D ? p->n : p->batch, p->op == GENSOR_OP_CONV2D ? p->c : p->M,
                              p->op == GENSOR_OP_CONV2D ? p->h : p->N, p->op == GENSOR_OP_CONV2D ? p->w : p->K,
                              p->op == GENSOR_OP_CONV2D ? p->k : 0, p->op == GENSOR_OP_CONV2D ? p->r : 0,
@@ -213,7 +247,10 @@ gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, int view_m
   std::lock_guard<std::mutex> lock(g_memo_mutex);
   auto it = g_memo.find(key);
   if (it != g_memo.end()) { *out = it->second; return GENSOR_OK; }
-  gensor_status st = construct_internal(p, nullptr, nullptr, 0, vec_ok, view_mode, out);
+  gensor_construct_opts opts;
+  std::memset(&opts, 0, sizeof(opts));
+  opts.no_split_k = no_split ? 1 : 0;
+  gensor_status st = construct_internal(p, nullptr, &opts, 0, vec_ok, view_mode, out);
   if (st == GENSOR_OK) g_memo[key] = *out;
   return st;
 }
@@ -222,19 +259,29 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
                   const void* A, int64_t lda, int64_t strideA, const void* B, int64_t ldb, int64_t strideB,
                   float beta, void* C, int64_t ldc, int64_t strideC, void* workspace, size_t workspace_bytes, void* stream) {
   const bool vec_ok = vector_ok(v, A, lda, strideA, B, ldb, strideB);
-  (void)workspace; (void)workspace_bytes;      // no kernel launched from here uses one
+  const bool ws_aligned = workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u) == 0;
   gensor_schedule local;
+  const bool constructed = !s;
+  const int mode = !v.pointwise ? VIEW_GENERAL : (v.cstride > 1 && v.bsrc == B_NC ? VIEW_PREPASS : VIEW_DEFAULT);
   if (!s) {
-    const int mode = !v.pointwise ? VIEW_GENERAL : (v.cstride > 1 && v.bsrc == B_NC ? VIEW_PREPASS : VIEW_DEFAULT);
-    gensor_status st = memoised_schedule(p, vec_ok, mode, &local);
+    // split-k schedules are ranked only for a caller that brought a workspace
+    gensor_status st = memoised_schedule(p, vec_ok, mode, !ws_aligned, &local);
     if (st != GENSOR_OK) return st;
     s = &local;
   }
   const InstanceDesc* d = find_instance(s, v);
+  if (constructed && d && s->split_k > 1 && workspace_bytes < split_plan(*d, v, s->split_k).bytes) {
+    // the workspace is too small for the split the ranking chose: the best unsplit schedule instead
+    gensor_status st = memoised_schedule(p, vec_ok, mode, true, &local);
+    if (st != GENSOR_OK) return st;
+    d = find_instance(s, v);
+  }
   if (!d) return GENSOR_ERR_NO_SCHEDULE;
   if (d->vec && !vec_ok) return GENSOR_ERR_NO_SCHEDULE;          // schedule asks for vector accesses the operands cannot give
   if (d->direct && !d->units && v.K % d->bk != 0) return GENSOR_ERR_NO_SCHEDULE;
-  if (s->split_k > 1) return GENSOR_ERR_UNSUPPORTED;
+  if (s->split_k < 1 || !split_allowed(*d, v, s->split_k)) return GENSOR_ERR_NO_SCHEDULE;
+  SplitPlan sp = split_plan(*d, v, s->split_k);
+  if (sp.split > 1 && (!ws_aligned || workspace_bytes < sp.bytes)) return GENSOR_ERR_WORKSPACE;
   // 32-bit offsets inside one workgroup tile
   const int64_t lim = 0x7fffffffll;
   if ((int64_t)(d->bm + 1) * lda * v.esize >= lim || (int64_t)(d->bm + 1) * ldc * v.osize >= lim) return GENSOR_ERR_UNSUPPORTED;
@@ -254,6 +301,15 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
   a.panel = s->wg_remap > 0 ? s->wg_remap : 1;
   if (a.panel > a.tiles_m) a.panel = a.tiles_m;
   if ((int64_t)a.tiles_m * a.tiles_n * a.batch > INT32_MAX) return GENSOR_ERR_UNSUPPORTED;
+  a.split = sp.split;
+  a.whole = (int32_t)sp.whole;
+  if (sp.split > 1) {
+    a.counters = (uint32_t*)workspace;
+    a.partials = (float*)((char*)workspace + sp.counter_bytes);
+    const int n = (int)(sp.counter_bytes / 4);
+    hipLaunchKernelGGL(clear_counters, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, a.counters, n);
+    if (hipGetLastError() != hipSuccess) return GENSOR_ERR_DEVICE;
+  }
   if (d->units) {
     ConvPlan pl;
     if (!conv_patch_plan(*d, v, &pl)) return GENSOR_ERR_NO_SCHEDULE;
@@ -265,7 +321,7 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
     a.cC = (int32_t)p->c; a.cH = (int32_t)p->h; a.cW = (int32_t)p->w; a.cR = (int32_t)p->r; a.cS = (int32_t)p->s;
     a.cP = (int32_t)v.P; a.cQ = (int32_t)v.Q; a.cStride = (int32_t)p->stride; a.cPad = (int32_t)p->pad;
   }
-  hipError_t e = d->launch(a, (hipStream_t)stream);
+  hipError_t e = sp.split > 1 ? d->launch_split(a, (hipStream_t)stream) : d->launch(a, (hipStream_t)stream);
   return e == hipSuccess ? GENSOR_OK : GENSOR_ERR_DEVICE;
 }
 }  // namespace

@@ -38,6 +38,16 @@ void schedule_from_instance(const InstanceDesc& d, gensor_schedule* s);
 bool instance_serves(const InstanceDesc& d, const GemmView& v);
 const InstanceDesc* find_instance(const gensor_schedule* s, const GemmView& v);
 
+// Workgroups and workspace of a split-k launch.
+struct SplitPlan {
+  int split;               // parts per split tile (1: nothing is split)
+  int64_t whole;           // tiles computed by one workgroup each
+  int64_t counter_bytes;   // arrival counters at the start of the workspace, padded to 256 bytes
+  size_t bytes;            // counters + partial tiles
+};
+SplitPlan split_plan(const InstanceDesc& d, const GemmView& v, int split);
+bool split_allowed(const InstanceDesc& d, const GemmView& v, int split);
+
 // gensor_construct with two more inputs: whether the operands allow 16-byte vector accesses
 // and the view (ViewMode) a pointwise convolution is taken in.
 gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, const gensor_construct_opts* opts,

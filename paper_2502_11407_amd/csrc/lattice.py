@@ -20,6 +20,11 @@ def _convp(dt, out, bm, bn, bkc, wm, wn, units, stages=2):
     return _inst(dt, out, bm, bn, bkc, wm, wn, 32, 1, 1, "CONV", 1, stages, 1, units)
 
 
+def splittable(d):
+    """Instances also compiled with split tiles (split-k): plainly fetched operands, vector loads, double buffer."""
+    return d["bsrc"] in ("KC", "NC") and d["vec"] == 1 and d["stages"] == 2 and not d["units"]
+
+
 def lattice():
     out = []
     # 16-bit inputs, fp32 output: (BM, BN, BK, WM, WN, MB, VM, VN)

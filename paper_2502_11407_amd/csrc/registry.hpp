@@ -20,6 +20,7 @@ struct InstanceDesc {
   int lds_bytes, threads, kg;           // kg: k consumed per fragment read (lds_bytes 0: set per problem)
   int units;                            // patch-staged convolution: transpose units per thread
   hipError_t (*launch)(const KernelArgs&, hipStream_t);
+  hipError_t (*launch_split)(const KernelArgs&, hipStream_t);   // the same instance with split tiles; null if not compiled
 };
 
 extern const InstanceDesc g_instances[];
@@ -40,13 +41,15 @@ hipError_t allow_dynamic_lds(K kernel, int bytes, std::atomic<uint64_t>& done) {
   return hipSuccess;
 }
 
-template <typename C>
+template <typename C, bool SPLIT = false>
 hipError_t launch_instance(const KernelArgs& a, hipStream_t st) {
   static std::atomic<uint64_t> done{0};
-  hipError_t e = allow_dynamic_lds(contraction_kernel<C>, C::LDS_BYTES, done);
+  hipError_t e = allow_dynamic_lds(contraction_kernel<C, SPLIT>, C::LDS_BYTES, done);
   if (e != hipSuccess) return e;
-  const unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.batch;
-  hipLaunchKernelGGL(contraction_kernel<C>, dim3(grid), dim3(C::THREADS), C::LDS_BYTES, st, a);
+  // one workgroup per whole tile and, in a split launch, a.split per tile behind them
+  const unsigned tiles = (unsigned)a.tiles_m * (unsigned)a.tiles_n * (unsigned)a.batch;
+  const unsigned grid = SPLIT ? (unsigned)a.whole + (tiles - (unsigned)a.whole) * (unsigned)a.split : tiles;
+  hipLaunchKernelGGL((contraction_kernel<C, SPLIT>), dim3(grid), dim3(C::THREADS), C::LDS_BYTES, st, a);
   return hipGetLastError();
 }
 

@@ -214,6 +214,18 @@ def unbalanced_gemm(index: int, dtype: str = "f16") -> GemmWorkload:
                          lambda s: uniform_pm1(_seed(6 + index, 1), s, dtype))
 
 
+# Few output tiles and a deep reduction, [M, K, N], transB: the shapes a split along k exists for (the other
+# extreme of "unbalanced" from the paper's tall ones; not in its operator table).
+DEEP_K_GEMMS = [("f16", 512, 32768, 512, 1), ("f16", 256, 65536, 256, 0), ("f16", 1024, 8192, 1024, 1), ("f32", 256, 16384, 256, 1)]
+
+
+def deep_k_gemm(index: int) -> GemmWorkload:
+    dtype, M, K, N, transB = DEEP_K_GEMMS[index]
+    return gemm_workload(f"gemm_{M}x{K}x{N}_{dtype}_deepk", dtype, M, N, K, 0, transB,
+                         lambda s: uniform_pm1(_seed(20 + index, 0), s, dtype),
+                         lambda s: uniform_pm1(_seed(20 + index, 1), s, dtype))
+
+
 GEMV_SHAPES = [(16384, 16384), (16384, 8192), (16384, 1000)]                      # V1-V3: [M, N]
 POOL_SHAPES = [(16, 48, 48, 48, 2, 2), (128, 168, 83, 83, 2, 2), (128, 617, 21, 21, 3, 2)]   # P1-P3: n, c, h, w, F, S
 PAPER_CONVS = [(128, 256, 30, 30, 256, 3, 2), (128, 128, 28, 28, 128, 3, 1), (128, 128, 58, 58, 128, 3, 2)]   # C1-C3: n, c, h, w, k, r, S

@@ -279,9 +279,11 @@ def _instances_for(gs, p):
     for idx in range(gs.num_instances()):
         s = gs.instance_schedule(idx, p)
         if s is not None:
+            # also compiled with split tiles: plainly fetched operands, vector loads, double buffer
+            split_ok = int(p.op != 2 and s.vec_bytes == 16 and s.stages == 2)
             out.append(oc.Instance(idx, s.tile[0][0], s.tile[1][0], s.tile[2][0], s.tile[0][1], s.tile[1][1],
                                    s.tile[2][1], s.vthread[0], s.vthread[1], 1 if s.vec_bytes == 16 else 0,
-                                   s.stages, s.direct_lds))
+                                   s.stages, s.direct_lds, split_ok))
     return out
 
 
@@ -320,6 +322,13 @@ def test_cpp_cost_model_and_pick_equal_oracle():
             s = gs.instance_schedule(i.id, p)
             want = oc.predict_us(view, HW, i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn, i.vec, i.stages, i.direct)
             assert gs.predict_us(s, p) == want
+            for split in (2, 3, 8):
+                s.split_k = split
+                assert gs.predict_us(s, p) == oc.predict_us(view, HW, i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn,
+                                                            i.vec, i.stages, i.direct, split)
+                # a workspace is asked for exactly where the instance exists with split tiles and the split applies
+                if p.op != 2:
+                    assert (gs.workspace_bytes(p, s) > 0) <= bool(i.split_ok)
         # gensor_construct assumes aligned dense operands: vector accesses iff the contiguous extents are whole vectors
         epc = 16 // view.e
         vec_ok = view.bsrc == 2 or (view.K % epc == 0 and (view.bsrc == 0 or view.N % epc == 0))
@@ -327,7 +336,7 @@ def test_cpp_cost_model_and_pick_equal_oracle():
             s = gs.construct(p, seed=seed)
             got, us, scored = oc.construct(view, HW, OPTS, seed, insts, vec_ok)
             assert got is not None
-            assert (s.kernel_id, s.predicted_us, s.states_scored) == (got.id, us, scored)
+            assert (s.kernel_id, s.predicted_us, s.states_scored, s.split_k) == (got.id, us, scored, got.split)
             assert s.chains == 1024 and 0 < s.iterations <= 100
             assert s.construct_s < 10.0
             # the schedule names a compiled instance that serves the problem

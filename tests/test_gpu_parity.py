@@ -644,3 +644,120 @@ def test_random_conv_geometries_with_constructed_schedules(gs, dtype):
         gs.conv2d(p, gs.to_device(I, dtype), gs.to_device(W, dtype), dO, None, gs.conv_workspace(p))
         torch.cuda.synchronize()
         assert np.array_equal(gs.to_host_f64(dO), want), f"case {case}"
+
+
+# ----------------------------------------------------------------------------------------------------------
+# split-k: tiles computed by several workgroups that exchange partial sums through the workspace
+# ----------------------------------------------------------------------------------------------------------
+def _split_schedules(gs, p, split, want_tiles):
+    """Schedules of the instances that serve `p`, exist with split tiles and have one of the wanted (BM, BN)."""
+    out = []
+    for idx in range(gs.num_instances()):
+        s = gs.instance_schedule(idx, p)
+        if s is None or (s.tile[0][0], s.tile[1][0]) not in want_tiles:
+            continue
+        if s.direct_lds and p.K % s.tile[2][0]:
+            continue                                   # direct staging takes whole k tiles only
+        s.split_k = split
+        if gs.workspace_bytes(p, s) > 0:
+            out.append(s)
+    return out
+
+
+def _run_split(gs, p, s, dtype, A, B, ws, alpha=1.0, beta=0.0, C0=None, out_dtype="f32"):
+    import torch
+    batch = A.shape[0] if A.ndim == 3 else 1
+    dA, dB = gs.to_device(A, dtype), gs.to_device(B, dtype)
+    shape = (batch, p.M, p.N) if batch > 1 else (p.M, p.N)
+    dC = gs.to_device(C0, out_dtype) if C0 is not None else gs.empty_device(shape, out_dtype).fill_(float("nan"))
+    (gs.bmm if batch > 1 else gs.gemm)(p, dA, dB, dC, alpha, beta, s, workspace=ws)
+    torch.cuda.synchronize()
+    return gs.to_host_f64(dC)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,M,N,K,tb,batch,split,tiles", [
+    ("f16", 256, 256, 2048, 1, 1, 8, {(256, 256), (128, 128), (64, 64)}),     # one to sixteen tiles, all split
+    ("f16", 200, 136, 1000, 0, 1, 3, {(128, 128), (64, 64), (32, 32)}),       # ragged tiles, k tail, parts on different XCDs
+    ("bf16", 192, 320, 1536, 1, 3, 2, {(128, 128), (64, 128), (64, 64)}),     # batched
+    ("f32", 130, 72, 520, 0, 1, 4, {(64, 64), (32, 32)}),
+    ("f16", 544, 544, 512, 1, 1, 2, {(32, 32)}),                              # 289 tiles: 256 whole, 33 split
+    ("f16", 1024, 1088, 256, 0, 1, 4, {(64, 64)}),                            # 272 tiles: 256 whole, 16 split four ways
+    ("f32", 64, 64, 4096, 1, 1, 16, {(64, 64), (32, 32)}),                    # the deepest split
+])
+def test_split_k_bit_exact_on_integers(gs, dtype, M, N, K, tb, batch, split, tiles):
+    p = gs.gemm_problem(dtype, M, N, K, 0, tb, batch)
+    scheds = _split_schedules(gs, p, split, tiles)
+    assert scheds
+    shp = lambda r, c: (batch, r, c) if batch > 1 else (r, c)
+    A = inputs.small_ints(31, shp(M, K), dtype, -2, 2)
+    B = inputs.small_ints(32, shp(N, K) if tb else shp(K, N), dtype, -2, 2)
+    A2 = inputs.small_ints(33, shp(M, K), dtype, -2, 2)
+    C0 = inputs.small_ints(34, shp(M, N), "f32", -3, 3)
+    ref = lambda a: np.stack([ops.gemm(a[b], B[b], dtype, transB=tb, alpha=2.0, beta=-1.0, C0=C0[b]) for b in range(batch)]) \
+        if batch > 1 else ops.gemm(a, B, dtype, transB=tb, alpha=2.0, beta=-1.0, C0=C0)
+    want, want2 = ref(A), ref(A2)
+    assert np.abs(want).max() < 2 ** 23
+    for s in scheds:
+        print("instance", s.kernel_id, s.describe()["tile_m"], s.describe()["tile_n"], "split", split, flush=True)
+        ws = gs.gemm_workspace(p, s)
+        ws.fill_(0xAB)                                  # whatever the workspace holds, counters included
+        # the same workspace serves call after call: the second must not see what the first left in it
+        assert np.array_equal(_run_split(gs, p, s, dtype, A2, B, ws, 2.0, -1.0, C0), want2)
+        assert np.array_equal(_run_split(gs, p, s, dtype, A, B, ws, 2.0, -1.0, C0), want)
+
+
+@pytest.mark.gpu
+def test_split_k_real_values_and_16_bit_output(gs):
+    M, N, K = 384, 256, 8192
+    for dtype, out_dtype, tb in (("f16", "f32", 1), ("f16", "f16", 0), ("bf16", "bf16", 1), ("f32", "f32", 0)):
+        p = gs.gemm_problem(dtype, M, N, K, 0, tb, 1, out_dtype)
+        A = inputs.uniform_pm1(41, (M, K), dtype)
+        B = inputs.uniform_pm1(42, (N, K) if tb else (K, N), dtype)
+        want = ops.gemm(A, B, dtype, transB=tb)
+        for split in (2, 5):
+            for s in _split_schedules(gs, p, split, {(128, 128), (64, 64)})[:3]:
+                got = _run_split(gs, p, s, dtype, A, B, gs.gemm_workspace(p, s), out_dtype=out_dtype)
+                err = ops.rel_frobenius(got, want)
+                print(dtype, out_dtype, "instance", s.kernel_id, "split", split, "rel frobenius", err, flush=True)
+                assert err <= (TOL[dtype] if out_dtype == "f32" else 2e-3)
+                # two parts are summed in one order, more parts in part order: the result is reproducible
+                again = _run_split(gs, p, s, dtype, A, B, gs.gemm_workspace(p, s), out_dtype=out_dtype)
+                assert np.array_equal(got, again)
+
+
+@pytest.mark.gpu
+def test_split_k_constructed_for_deep_k_and_workspace_rules(gs):
+    import torch
+    M, N, K = 512, 512, 16384
+    p = gs.gemm_problem("f16", M, N, K, 0, 1)
+    s = gs.construct(p)
+    assert s.split_k > 1 and gs.workspace_bytes(p, s) > 0
+    A, B = inputs.uniform_pm1(51, (M, K), "f16"), inputs.uniform_pm1(52, (N, K), "f16")
+    want = ops.gemm(A, B, "f16", transB=1)
+    ws = gs.gemm_workspace(p, s)
+    assert ops.rel_frobenius(_run_split(gs, p, s, "f16", A, B, ws), want) <= TOL["f16"]
+    # no schedule named: the library constructs one; with a workspace it may split, without one it does not
+    assert ops.rel_frobenius(_run_split(gs, p, None, "f16", A, B, ws), want) <= TOL["f16"]
+    assert ops.rel_frobenius(_run_split(gs, p, None, "f16", A, B, None), want) <= TOL["f16"]
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    assert ops.rel_frobenius(_run_split(gs, p, None, "f16", A, B, small), want) <= TOL["f16"]
+    # a named split schedule needs its workspace: missing, too small, misaligned
+    for bad in (None, small, ws[16:]):
+        with pytest.raises(gs.GensorError) as e:
+            _run_split(gs, p, s, "f16", A, B, bad)
+        assert e.value.status == 4
+    # more parts than k tiles, or an instance without the split path
+    s.split_k = 16
+    q = gs.gemm_problem("f16", M, N, 8 * s.tile[2][0], 0, 1)
+    with pytest.raises(gs.GensorError) as e:
+        _run_split(gs, q, s, "f16", A[:, :q.K].copy(), B[:, :q.K].copy(), ws)
+    assert e.value.status == 3
+    # a tile count that is a whole number of rounds has nothing to split: runs as it is, no workspace
+    r = gs.gemm_problem("f16", 512, 512, 256, 0, 1)
+    s32 = [x for x in (gs.instance_schedule(i, r) for i in range(gs.num_instances()))
+           if x is not None and (x.tile[0][0], x.tile[1][0]) == (32, 32) and x.vec_bytes == 16 and x.stages == 2][0]
+    s32.split_k = 2
+    assert gs.workspace_bytes(r, s32) == 0
+    Ar, Br = inputs.small_ints(53, (512, 256), "f16", -2, 2), inputs.small_ints(54, (512, 256), "f16", -2, 2)
+    assert np.array_equal(_run_split(gs, r, s32, "f16", Ar, Br, None), ops.gemm(Ar, Br, "f16", transB=1))
