@@ -330,7 +330,7 @@ def _full_size_case(gs, name):
         out = gs.empty_device((w.batch, w.M, w.N) if w.batch > 1 else (w.M, w.N))
         out.fill_(float("nan"))
         dA, dB = gs.to_device(w.A, w.dtype), gs.to_device(w.B, w.dtype)
-        (gs.bmm if w.batch > 1 else gs.gemm)(p, dA, dB, out, 1.0, 0.0, s)
+        (gs.bmm if w.batch > 1 else gs.gemm)(p, dA, dB, out, 1.0, 0.0, s, workspace=gs.gemm_workspace(p, s))
         torch.cuda.synchronize()
         co = inputs.sample_indices(21, (w.batch, w.M, w.N), 1500)
         # whole first / last rows and columns as well: tile edges and the ragged last tile
@@ -761,3 +761,15 @@ def test_split_k_constructed_for_deep_k_and_workspace_rules(gs):
     assert gs.workspace_bytes(r, s32) == 0
     Ar, Br = inputs.small_ints(53, (512, 256), "f16", -2, 2), inputs.small_ints(54, (512, 256), "f16", -2, 2)
     assert np.array_equal(_run_split(gs, r, s32, "f16", Ar, Br, None), ops.gemm(Ar, Br, "f16", transB=1))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("index", range(len(inputs.DEEP_K_GEMMS)))
+def test_deep_k_shapes_full_size_sampled(gs, index):
+    """The deep-k workloads bench.py times, with the constructed (split-k) schedule: sampled entries and tile
+    edges against the oracle, no unwritten output."""
+    w, s, got, want, finite = _full_size_case(gs, inputs.deep_k_gemm(index))
+    assert s.split_k > 1
+    err = ops.rel_frobenius(got, want)
+    print(w.name, "kernel", s.kernel_id, "split", s.split_k, "rel frobenius", err)
+    assert finite and err <= TOL[w.dtype]
