@@ -99,6 +99,7 @@ template <> __device__ inline void store_out<bf16_t>(void* p, int64_t i, float v
 // (the bits travel through a by-value argument: a bit cast applied directly to a vector
 // element expression reads element 0 whatever the index)
 __device__ inline float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ inline uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
 
 template <typename T, int MB> struct Mfma;
 template <> struct Mfma<f16_t, 32> {
@@ -228,19 +229,20 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   const int tiles_per_batch = args.tiles_m * args.tiles_n;
   const int total = tiles_per_batch * args.batch;
   int wg = blockIdx.x;
-  int part = 0, parts = 1;
+  int kpart = 0, kparts = 1;                // this workgroup's share of a split tile
   if constexpr (!SPLIT) {
     if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
   } else if (wg < args.whole) {
     if ((args.whole & 7) == 0) wg = (wg & 7) * (args.whole >> 3) + (wg >> 3);
   } else {
-    // the split tiles come last in launch order; the `split` workgroups of one tile are neighbours on one XCD
-    parts = args.split;
+    // the split tiles come last in launch order; with workgroup ids dealt round-robin to the XCDs the parts
+    // of one tile are neighbours on one XCD (a matter of locality only)
+    kparts = args.split;
     int u = wg - args.whole;
-    const int units = (total - args.whole) * parts;
+    const int units = (total - args.whole) * kparts;
     if ((units & 7) == 0) u = (u & 7) * (units >> 3) + (u >> 3);
-    wg = args.whole + u / parts;
-    part = u - (wg - args.whole) * parts;
+    wg = args.whole + u / kparts;
+    kpart = u - (wg - args.whole) * kparts;
   }
   const int bidx = wg / tiles_per_batch;
   int t = wg - bidx * tiles_per_batch;
@@ -257,14 +259,14 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   const int m0 = tile_m * BM;
   const int n0 = tile_n * BN;
 
-  // k range of this workgroup: the whole of K, or k tiles [part * nk / parts, (part + 1) * nk / parts) of a split
+  // k range of this workgroup: the whole of K, or k tiles [kpart * nk / kparts, (kpart + 1) * nk / kparts) of a split
   // tile.  The operand bases move to the first k of the range and Kx is its length, so everything below
   // sees a shorter contraction.
   int Kx = args.K;
   int64_t k_first = 0;
-  if (SPLIT && parts > 1) {
+  if (SPLIT && kparts > 1) {
     const int nk_all = (args.K + BK - 1) / BK;
-    const int kt0 = part * nk_all / parts, kt1 = (part + 1) * nk_all / parts;
+    const int kt0 = kpart * nk_all / kparts, kt1 = (kpart + 1) * nk_all / kparts;
     k_first = (int64_t)kt0 * BK;
     Kx = min(args.K, kt1 * BK) - kt0 * BK;
   }
@@ -798,48 +800,44 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     }
   }
 
-  // ---- epilogue: C = alpha * acc + beta * C through a buffer descriptor that starts at this
-  // tile's first element; rows outside the matrix fall out of its range, columns beyond it are
-  // sent out of range explicitly (they would alias the next row).  Lane l of a 32x32 block holds
-  // column l%32 and rows 8*(v/4) + 4*(l/32) + v%4 in acc[v] (16x16: column l%16, rows 4*(l/16) + v),
-  // so one element store of a wave covers two whole 128-byte row segments of C (four 64-byte
-  // ones for 16x16 blocks).  Accumulating the transposed block instead, for 16-byte vector stores
-  // of four columns per lane, measured slower everywhere (32 rows x 32 bytes per instruction:
-  // -3 % on the 4096^3 GEMM, -9 % on 8192x3072x768, -11 % on the store-bound K = 64 shapes).
-  if (SPLIT && parts > 1) {
-    // Split tile: every wave leaves its accumulators in this workgroup's slot (16 bytes per lane and store,
-    // a wave's store one contiguous KiB) and counts itself in.  The wave that finds the other parts-1 already
-    // counted adds their slots to its own registers and goes on to the epilogue; the others are done.  Nothing
-    // waits.  Two parts: own registers plus the other slot (the sum of two terms has one order).  More: the
-    // slots are summed from memory in part order, so the result does not depend on who came last.
+  // ---- split tile: exchange the partial sums; one wave per (tile, wave position) goes on to the epilogue
+  if (SPLIT && kparts > 1) {
+    // Every wave leaves its accumulators in this workgroup's slot (16 bytes per lane and store, a wave's store
+    // one contiguous KiB) and counts itself in.  The wave that finds the other parts-1 already counted adds
+    // their slots to its own registers and goes on to the epilogue; the others are done.  Nothing waits.
+    // Two parts: own registers plus the other slot (the sum of two terms has one order).  More: the slots are
+    // summed from memory in part order, so the result does not depend on who came last.
+    // The parts of a tile may run on different XCDs, whose L2s do not see each other's lines: the slot
+    // stores and loads carry the device-scope cache policy (write through / fetch again), a wave counts
+    // itself in only after its stores have completed, and the count is a device-scope atomic.  Nothing else
+    // in the kernel pays for this (a device-scope fence would write back and invalidate the whole L2 here).
     constexpr int NV = C::MBLK * C::NBLK * MF::NACC / 4;       // 16-byte groups per lane
     constexpr int SLOT_BYTES = BM * BN * 4;
     constexpr int DEVICE_SCOPE = 16;                           // sc1: the access is coherent across the whole device
-    const int64_t tile_slot = (int64_t)(wg - args.whole) * parts;
+    const int64_t tile_slot = (int64_t)(wg - args.whole) * kparts;
     auto slot = [&](int o) {
       return __builtin_amdgcn_make_buffer_rsrc((void*)((char*)args.partials + (tile_slot + o) * (int64_t)SLOT_BYTES), 0,
                                                (uint32_t)SLOT_BYTES, RSRC_FLAGS);
     };
-    const __amdgpu_buffer_rsrc_t own = slot(part);
+    const __amdgpu_buffer_rsrc_t own = slot(kpart);
 #pragma unroll
     for (int g = 0; g < NV; ++g) {
       const int b = g / (MF::NACC / 4), q = g % (MF::NACC / 4);
       u32x4 v;
 #pragma unroll
-      for (int x = 0; x < 4; ++x) v[x] = __builtin_bit_cast(uint32_t, (float)acc[b / C::NBLK][b % C::NBLK][4 * q + x]);
+      for (int x = 0; x < 4; ++x) v[x] = as_u32(acc[b / C::NBLK][b % C::NBLK][4 * q + x]);
       __builtin_amdgcn_raw_buffer_store_b128(v, own, (uint32_t)((g * C::THREADS + tid) * 16), 0, DEVICE_SCOPE);
       if (g % 8 == 7) __builtin_amdgcn_sched_barrier(0);
     }
-    // the slot's stores have completed (they write through to device scope) before the count
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // compiler ordering
+    __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0): this wave's slot stores have completed
     __builtin_amdgcn_sched_barrier(0);
     uint32_t before = 0;
     if (lane == 0) before = atomicAdd(args.counters + (int64_t)(wg - args.whole) * C::WAVES + wave, 1u);
     before = __builtin_amdgcn_readfirstlane(before);
-    if (before != (uint32_t)(parts - 1)) return;
+    if (before != (uint32_t)(kparts - 1)) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    const bool from_memory = parts > 2;
+    const bool from_memory = kparts > 2;
     if (from_memory) {
 #pragma unroll
       for (int i = 0; i < C::MBLK; ++i)
@@ -848,8 +846,8 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 #pragma unroll
           for (int v = 0; v < MF::NACC; ++v) acc[i][j][v] = 0.f;
     }
-    for (int o = 0; o < parts; ++o) {
-      if (!from_memory && o == part) continue;
+    for (int o = 0; o < kparts; ++o) {
+      if (!from_memory && o == kpart) continue;
       const __amdgpu_buffer_rsrc_t src = slot(o);
 #pragma unroll
       for (int g = 0; g < NV; ++g) {
@@ -861,6 +859,15 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       }
     }
   }
+
+  // ---- epilogue: C = alpha * acc + beta * C through a buffer descriptor that starts at this
+  // tile's first element; rows outside the matrix fall out of its range, columns beyond it are
+  // sent out of range explicitly (they would alias the next row).  Lane l of a 32x32 block holds
+  // column l%32 and rows 8*(v/4) + 4*(l/32) + v%4 in acc[v] (16x16: column l%16, rows 4*(l/16) + v),
+  // so one element store of a wave covers two whole 128-byte row segments of C (four 64-byte
+  // ones for 16x16 blocks).  Accumulating the transposed block instead, for 16-byte vector stores
+  // of four columns per lane, measured slower everywhere (32 rows x 32 bytes per instruction:
+  // -3 % on the 4096^3 GEMM, -9 % on 8192x3072x768, -11 % on the store-bound K = 64 shapes).
   typedef typename C::OutT OutT;
   constexpr int OS = ElemSize<OutT>::value;
   char* Cb = (char*)args.C + (int64_t)bidx * args.strideC * OS;
