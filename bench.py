@@ -172,6 +172,33 @@ def mfma_ceiling(gs, inputs, dtype, iters=20000):
     return flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
+def _graph_us(fn, launches=20, replays=10):
+    """Microseconds per launch when `launches` calls of fn are captured in one HIP graph and the graph is replayed:
+    the host's per-call cost (interpreter, binding, enqueue) is paid once at capture, so what remains is the
+    device's own time per launch.  For the launches of a few microseconds the eager event timing is the host's."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(launches):
+            fn()
+    for _ in range(3):
+        g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (launches * replays)
+
+
 def _median_ms(fn, steps, warmup=5, batches=5):
     import torch
     for _ in range(warmup):
@@ -259,10 +286,12 @@ def operator_table_rows(gs, inputs):
         dA, dx = gs.to_device(A, "f16"), gs.to_device(x, "f16")
         y = torch.empty(M, dtype=torch.float32, device="cuda")
         m = _median_ms(lambda: gs.gemv("f16", dA, dx, y), 30)
+        in_graph = _graph_us(lambda: gs.gemv("f16", dA, dx, y))
         nbytes = 2 * (M * N + N) + 4 * M
         sel = inputs.sample_indices(7, (M,), 64)[:, 0]
         err = ops.rel_frobenius(gs.to_host_f64(y)[sel], ops.gemv(np.ascontiguousarray(A[sel]), x, "f16"))
-        rows.append({"workload": f"gemv_{M}x{N}_f16", "us": m * 1e3, "tflops": 2.0 * M * N / (m * 1e-3) / 1e12,
+        rows.append({"workload": f"gemv_{M}x{N}_f16", "us": m * 1e3, "us_in_graph": in_graph,
+                     "GBs_in_graph": nbytes / (in_graph * 1e-6) / 1e9, "tflops": 2.0 * M * N / (m * 1e-3) / 1e12,
                      "algorithmic_GBs": nbytes / (m * 1e-3) / 1e9, "pct_of_hbm_peak": 100.0 * nbytes / (m * 1e-3) / 1e9 / HBM_GBS,
                      "parity_rel_frobenius_sampled": err})
         del dA, dx, A
@@ -273,11 +302,13 @@ def operator_table_rows(gs, inputs):
         dI = gs.to_device(I, "f16")
         O = gs.empty_device(shape)
         m = _median_ms(lambda: gs.avgpool2d("f16", dI, O, f, stride), 30)
+        in_graph = _graph_us(lambda: gs.avgpool2d("f16", dI, O, f, stride))
         nbytes = 2 * I.size + 4 * int(np.prod(shape))
         co = inputs.sample_indices(7, shape, 256)
         idx = torch.from_numpy(co).cuda()
         got = O[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].double().cpu().numpy()
         rows.append({"workload": "avgpool_%dx%dx%dx%d_f%d_s%d_f16" % (*I.shape, f, stride), "us": m * 1e3,
+                     "us_in_graph": in_graph, "GBs_in_graph": nbytes / (in_graph * 1e-6) / 1e9,
                      "algorithmic_GBs": nbytes / (m * 1e-3) / 1e9, "pct_of_hbm_peak": 100.0 * nbytes / (m * 1e-3) / 1e9 / HBM_GBS,
                      "parity_rel_frobenius_sampled": ops.rel_frobenius(got, ops.avgpool2d_at(I, "f16", co, f, stride))})
         del dI, O, I
@@ -402,11 +433,13 @@ def main():
             c = Case(gs, inputs, wl)
             m = c.time_median_ms(steps2, max(5, args.warmup // 4))
             cold, _ = c.time_cold_ms()
+            in_graph = _graph_us(c.launch)
             tf = wl.flops / (m * 1e-3) / 1e12
             nbytes = _algorithmic_bytes(wl, inputs)
             gb = nbytes / (m * 1e-3) / 1e9
             ceiling = min(PEAK_TFLOPS[wl.dtype], wl.flops / nbytes * HBM_GBS / 1e3)     # TFLOP/s
-            ops_out.append({"workload": wl.name, "dtype": wl.dtype, "us": m * 1e3, "cold_us": cold * 1e3, "tflops": tf,
+            ops_out.append({"workload": wl.name, "dtype": wl.dtype, "us": m * 1e3, "cold_us": cold * 1e3,
+                            "us_in_graph": in_graph, "tflops": tf,
                             "pct_of_mfma_peak": 100.0 * tf / PEAK_TFLOPS[wl.dtype],
                             "algorithmic_GBs": gb, "pct_of_hbm_peak": 100.0 * gb / HBM_GBS,
                             "roofline_ceiling_tflops": ceiling, "pct_of_roofline_ceiling": 100.0 * tf / ceiling,

@@ -773,3 +773,65 @@ def test_deep_k_shapes_full_size_sampled(gs, index):
     err = ops.rel_frobenius(got, want)
     print(w.name, "kernel", s.kernel_id, "split", s.split_k, "rel frobenius", err)
     assert finite and err <= TOL[w.dtype]
+
+
+@pytest.mark.gpu
+def test_operators_captured_in_a_graph_replay_like_eager_calls(gs):
+    """Every operator launch (the split-k pair of counter clear + kernel included) can be recorded into a HIP
+    graph: each replay, with eager work and synchronisations in between and fresh inputs written into the
+    captured buffers, gives what the eager call gives."""
+    import torch
+    M, N, K = 256, 192, 4096
+    p = gs.gemm_problem("f16", M, N, K, 0, 1)
+    s = [x for x in _split_schedules(gs, p, 4, {(64, 64)})][0]
+    ws = gs.gemm_workspace(p, s)
+    pc = gs.conv_problem("f16", 2, 16, 12, 12, 24, 3, 3, 1, 1)
+    dA, dB = gs.empty_device((M, K), "f16"), gs.empty_device((N, K), "f16")
+    dC, dC1 = gs.empty_device((M, N)), gs.empty_device((M, N))
+    dI, dW, dO = gs.empty_device((2, 16, 12, 12), "f16"), gs.empty_device((24, 16, 3, 3), "f16"), gs.empty_device((2, 24, 12, 12))
+    dx, dy = gs.empty_device((K,), "f16"), gs.empty_device((M,))
+    dP = gs.empty_device((2, 16, 6, 6))
+    cws = gs.conv_workspace(pc)
+
+    def launch_all():
+        gs.gemm(p, dA, dB, dC, 1.0, 0.0, s, workspace=ws)          # split-k: counter clear + kernel
+        gs.gemm(p, dA, dB, dC1, 1.0, 0.0, None)                    # schedule looked up per shape
+        gs.conv2d(pc, dI, dW, dO, None, cws)
+        gs.gemv("f16", dA, dx, dy)
+        gs.avgpool2d("f16", dI, dP, 2, 2)
+
+    def fill(seed):
+        dA.copy_(gs.to_device(inputs.small_ints(seed, (M, K), "f16", -2, 2), "f16"))
+        dB.copy_(gs.to_device(inputs.small_ints(seed + 1, (N, K), "f16", -2, 2), "f16"))
+        dI.copy_(gs.to_device(inputs.small_ints(seed + 2, (2, 16, 12, 12), "f16", -2, 2), "f16"))
+        dW.copy_(gs.to_device(inputs.small_ints(seed + 3, (24, 16, 3, 3), "f16", -2, 2), "f16"))
+        dx.copy_(gs.to_device(inputs.small_ints(seed + 4, (K,), "f16", -2, 2), "f16"))
+
+    outs = (dC, dC1, dO, dy, dP)
+    fill(60)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        launch_all()                                               # first use outside the capture (per-device set-up)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        launch_all()
+    for rep in range(4):
+        fill(70 + 10 * rep)
+        launch_all()
+        torch.cuda.synchronize()
+        eager = [o.clone() for o in outs]
+        for o in outs:
+            o.fill_(float("nan"))
+        ws.fill_(0x5A)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for name, o, e in zip(("gemm split-k", "gemm", "conv2d", "gemv", "avgpool2d"), outs, eager):
+            assert torch.equal(o, e), (rep, name)
+    # and the eager results are the oracle's (last inputs)
+    A = inputs.small_ints(100, (M, K), "f16", -2, 2)
+    B = inputs.small_ints(101, (N, K), "f16", -2, 2)
+    assert np.array_equal(gs.to_host_f64(dC), ops.gemm(A, B, "f16", transB=1))
