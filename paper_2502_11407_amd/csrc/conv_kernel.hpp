@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void subsample_input(const void* in, void* out
 // FMODE, how the filters are reordered on the way into the tile, is a template parameter: with all
 // three routes in one kernel the register allocation is the union of theirs (250 VGPRs, spills to
 // scratch) and every convolution shape measured ran 14 % slower.
-template <typename C, int FMODE>
+template <typename C, int FMODE, bool THROUGH>
 __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs args) {
   typedef typename C::T T;
   typedef Mfma<T, C::MB> MF;
@@ -451,27 +451,35 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
   typedef typename C::OutT OutT;
   constexpr int OS = ElemSize<OutT>::value;
   const __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void*)args.C, 0, (uint32_t)args.cOutBytes, RSRC_FLAGS);
+  // Cache policy of the stores (an immediate of the instruction, hence a template parameter; a run-time
+  // branch over two copies of the loop cost 1-4 %): write-through for a shallow reduction, where the stores
+  // are a large share of the launch (64 channels x 3x3, 64 filters: 17.9 -> 15.6 us), write-back for a deep
+  // one, where the L2 drains them under the next tile's work (reductions of 1152 and 2304: write-through
+  // measured 1.5-2.5 % slower).
+  {
+    constexpr int POLICY = THROUGH ? 16 : 0;
 #pragma unroll
-  for (int bj = 0; bj < C::NBLK; ++bj) {
-    const int col = n0 + block_col(bj) + frow;
-    const int img = col / PQ;
-    const int cbase = img * args.M * PQ + (col - img * PQ);
+    for (int bj = 0; bj < C::NBLK; ++bj) {
+      const int col = n0 + block_col(bj) + frow;
+      const int img = col / PQ;
+      const int cbase = img * args.M * PQ + (col - img * PQ);
 #pragma unroll
-    for (int bi = 0; bi < C::MBLK; ++bi)
+      for (int bi = 0; bi < C::MBLK; ++bi)
 #pragma unroll
-      for (int v = 0; v < MF::NACC; ++v) {
-        const int rr = (MB == 32) ? 8 * (v / 4) + 4 * fgrp + (v % 4) : 4 * fgrp + v;
-        const int row = m0 + block_row(bi) + rr;
-        const uint32_t off = (row < args.M && col < args.N) ? (uint32_t)((cbase + row * PQ) * OS) : OOB;
-        const float val = acc[bi][bj][v];
-        if constexpr (OS == 4) {
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), rs_out, off, 0, 0);
-        } else {
-          uint16_t bits;
-          store_out<OutT>(&bits, 0, val);
-          __builtin_amdgcn_raw_buffer_store_b16(bits, rs_out, off, 0, 0);
+        for (int v = 0; v < MF::NACC; ++v) {
+          const int rr = (MB == 32) ? 8 * (v / 4) + 4 * fgrp + (v % 4) : 4 * fgrp + v;
+          const int row = m0 + block_row(bi) + rr;
+          const uint32_t off = (row < args.M && col < args.N) ? (uint32_t)((cbase + row * PQ) * OS) : OOB;
+          const float val = acc[bi][bj][v];
+          if constexpr (OS == 4) {
+            __builtin_amdgcn_raw_buffer_store_b32(as_u32(val), rs_out, off, 0, POLICY);
+          } else {
+            uint16_t bits;
+            store_out<OutT>(&bits, 0, val);
+            __builtin_amdgcn_raw_buffer_store_b16(bits, rs_out, off, 0, POLICY);
+          }
         }
-      }
+    }
   }
 }
 

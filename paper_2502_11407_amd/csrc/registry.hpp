@@ -55,22 +55,29 @@ hipError_t launch_instance(const KernelArgs& a, hipStream_t st) {
 
 // patch-staged convolution: the LDS size depends on the problem (a.cStageBytes per LDS stage
 // plus, unless the filter is 1x1 or 3x3, one raw filter region of BM * R*S*BKC elements).
-template <typename C, int FMODE>
+template <typename C, int FMODE, bool THROUGH>
 hipError_t launch_conv_route(const KernelArgs& a, hipStream_t st, int raw_bytes) {
   static std::atomic<uint64_t> done{0};
-  hipError_t e = allow_dynamic_lds(conv_patch_kernel<C, FMODE>, 160 * 1024, done);
+  hipError_t e = allow_dynamic_lds(conv_patch_kernel<C, FMODE, THROUGH>, 160 * 1024, done);
   if (e != hipSuccess) return e;
   const unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n;
-  hipLaunchKernelGGL((conv_patch_kernel<C, FMODE>), dim3(grid), dim3(C::THREADS), C::LSTAGES * a.cStageBytes + raw_bytes, st, a);
+  hipLaunchKernelGGL((conv_patch_kernel<C, FMODE, THROUGH>), dim3(grid), dim3(C::THREADS), C::LSTAGES * a.cStageBytes + raw_bytes, st, a);
   return hipGetLastError();
+}
+
+// The output is stored write-through when the reduction is shallow (the stores are then a large share of
+// the launch), write-back otherwise.
+template <typename C, bool THROUGH>
+hipError_t launch_conv_policy(const KernelArgs& a, hipStream_t st) {
+  const int rs = a.cR * a.cS;
+  if (rs == 9) return launch_conv_route<C, 2, THROUGH>(a, st, 0);       // 3x3 and 1x1 reorder their filters in registers
+  if (rs == 1) return launch_conv_route<C, 1, THROUGH>(a, st, 0);
+  return launch_conv_route<C, 0, THROUGH>(a, st, C::BM * rs * C::BKC * C::ES);      // the others through a raw LDS region
 }
 
 template <typename C>
 hipError_t launch_conv_instance(const KernelArgs& a, hipStream_t st) {
-  const int rs = a.cR * a.cS;
-  if (rs == 9) return launch_conv_route<C, 2>(a, st, 0);       // 3x3 and 1x1 reorder their filters in registers
-  if (rs == 1) return launch_conv_route<C, 1>(a, st, 0);
-  return launch_conv_route<C, 0>(a, st, C::BM * rs * C::BKC * C::ES);      // the others through a raw LDS region
+  return a.K <= 1024 ? launch_conv_policy<C, true>(a, st) : launch_conv_policy<C, false>(a, st);
 }
 
 }  // namespace gensor
