@@ -39,7 +39,17 @@ __device__ inline float wave_sum(float v) {
 // ---------------------------------------------------------------------------------------
 constexpr int GEMV_PANEL_BYTES = 32768;
 
-template <typename T>
+// STREAM: the rows of A are read with the non-temporal hint.  A matrix larger than the 256 MiB Infinity
+// Cache only evicts itself from it (16384^2 fp16, 512 MiB: 98.7 -> 89.4 us with the hint); one that fits is
+// served from it on repeated calls and loses that with the hint (16384 x 8192: 41.8 -> 45.6 us), so the
+// launch sets it by the size of A.
+template <bool STREAM>
+__device__ inline u32x4 load_row_vector(const char* p) {
+  if constexpr (STREAM) return __builtin_nontemporal_load((const u32x4*)p);
+  else return *(const u32x4*)p;
+}
+
+template <typename T, bool STREAM>
 __global__ __launch_bounds__(256) void gemv_vec_kernel(const char* A, int64_t lda, const char* x, float* y, int M, int N,
                                                        float alpha, float beta) {
   constexpr int ES = ElemSize<T>::value, EPC = 16 / ES, PANEL = GEMV_PANEL_BYTES / ES, UNROLL = 4;
@@ -82,8 +92,8 @@ __global__ __launch_bounds__(256) void gemv_vec_kernel(const char* A, int64_t ld
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u) {
         const int64_t off = ((int64_t)p0 + (int64_t)(c + u * 64) * EPC) * ES;
-        va[u] = *(const u32x4*)(a0 + off);
-        vb[u] = *(const u32x4*)(a1 + off);
+        va[u] = load_row_vector<STREAM>(a0 + off);
+        vb[u] = load_row_vector<STREAM>(a1 + off);
       }
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u) {
@@ -242,8 +252,12 @@ template <typename T>
 hipError_t launch_gemv(const void* A, int64_t lda, const void* x, float* y, int64_t M, int64_t N, float alpha, float beta, hipStream_t st) {
   constexpr int ES = ElemSize<T>::value, EPC = 16 / ES;
   const bool vec = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(x)) & 15u) == 0 && lda % EPC == 0;
-  if (vec)
-    hipLaunchKernelGGL(gemv_vec_kernel<T>, dim3((unsigned)((M + 7) / 8)), dim3(256), 0, st, (const char*)A, lda, (const char*)x, y,
+  const bool stream = M * lda * ES > (int64_t)256 * 1024 * 1024;      // larger than the Infinity Cache
+  if (vec && stream)
+    hipLaunchKernelGGL((gemv_vec_kernel<T, true>), dim3((unsigned)((M + 7) / 8)), dim3(256), 0, st, (const char*)A, lda, (const char*)x, y,
+                       (int)M, (int)N, alpha, beta);
+  else if (vec)
+    hipLaunchKernelGGL((gemv_vec_kernel<T, false>), dim3((unsigned)((M + 7) / 8)), dim3(256), 0, st, (const char*)A, lda, (const char*)x, y,
                        (int)M, (int)N, alpha, beta);
   else
     hipLaunchKernelGGL(gemv_scalar_kernel<T>, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, (const char*)A, lda, (const char*)x, y,
