@@ -835,3 +835,28 @@ def test_operators_captured_in_a_graph_replay_like_eager_calls(gs):
     A = inputs.small_ints(100, (M, K), "f16", -2, 2)
     B = inputs.small_ints(101, (N, K), "f16", -2, 2)
     assert np.array_equal(gs.to_host_f64(dC), ops.gemm(A, B, "f16", transB=1))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M,N,K,split", [(384, 384, 2048, 3), (512, 512, 4096, 8), (192, 320, 1536, 5)])
+def test_split_k_many_calls_on_one_workspace_stay_exact(gs, M, N, K, split):
+    """Two hundred calls alternating between two input sets on one workspace, parts of a tile on one XCD
+    (unit count a multiple of 8) and spread over several (not a multiple): every result is the oracle's,
+    so no call ever reads a partial sum or a count that an earlier call left behind."""
+    import torch
+    p = gs.gemm_problem("f16", M, N, K, 0, 1)
+    s = _split_schedules(gs, p, split, {(128, 128), (64, 64)})[0]
+    ws = gs.gemm_workspace(p, s)
+    sets = []
+    for seed in (81, 91):
+        A = inputs.small_ints(seed, (M, K), "f16", -2, 2)
+        B = inputs.small_ints(seed + 1, (N, K), "f16", -2, 2)
+        sets.append((gs.to_device(A, "f16"), gs.to_device(B, "f16"), torch.from_numpy(ops.gemm(A, B, "f16", transB=1)).float().cuda()))
+    dC = gs.empty_device((M, N))
+    bad = torch.zeros((), dtype=torch.int64, device="cuda")
+    for it in range(200):
+        dA, dB, want = sets[it & 1] if it % 7 else sets[1 - (it & 1)]
+        gs.gemm(p, dA, dB, dC, 1.0, 0.0, s, workspace=ws)
+        bad += (dC != want).sum()
+    torch.cuda.synchronize()
+    assert int(bad) == 0
