@@ -372,6 +372,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=300,
                     help="untimed launches first; the shader clock needs tens of milliseconds of load to settle")
     ap.add_argument("--only-headline", action="store_true", help="skip the other operator shapes and the CPU legs")
+    ap.add_argument("--launch-only", default="",
+                    help="comma-separated workload names (cfg1..cfg5_1x1s2, u0..u4, d0..d3): construct, launch each "
+                         "20 times and exit -- what a hardware-counter pass over one of the other shapes runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy, the known-size reference for HBM byte counters")
     args = ap.parse_args()
@@ -392,6 +395,19 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.launch_only:
+        for name in args.launch_only.split(","):
+            wl = (inputs.unbalanced_gemm(int(name[1:])) if name[0] == "u" else
+                  inputs.deep_k_gemm(int(name[1:])) if name[0] == "d" else inputs.all_configs()[name])
+            c = Case(gs, inputs, wl)
+            for _ in range(20):
+                c.launch()
+            torch.cuda.synchronize()
+            print(name, "kernel", c.sched.kernel_id, "split_k", c.sched.split_k)
+            del c
+            torch.cuda.empty_cache()
+        return
 
     w = inputs.config2_gemm_f16()
     head = Case(gs, inputs, w)
