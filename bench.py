@@ -435,6 +435,8 @@ def main():
                      "frac": tflops / peak, "traffic": traffic},
     }
     if not args.only_headline:
+        # one launch at a time (graph replay, no overlap between the tail of one launch and the head of the next)
+        line["us_in_graph"] = _graph_us(head.launch, launches=10, replays=10)
         ceil_tf = mfma_ceiling(gs, inputs, w.dtype)
         line["mfma_only_kernel_same_operand_distribution"] = {
             "tflops": ceil_tf, "frac_of_it": tflops / ceil_tf,
