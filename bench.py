@@ -172,7 +172,7 @@ def mfma_ceiling(gs, inputs, dtype, iters=20000):
     return flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
-def _graph_us(fn, launches=20, replays=10):
+def _graph_us(fn, launches=20, replays=10, warm_replays=3):
     """Microseconds per launch when `launches` calls of fn are captured in one HIP graph and the graph is replayed:
     the host's per-call cost (interpreter, binding, enqueue) is paid once at capture, so what remains is the
     device's own time per launch.  For the launches of a few microseconds the eager event timing is the host's."""
@@ -187,9 +187,8 @@ def _graph_us(fn, launches=20, replays=10):
     with torch.cuda.graph(g):
         for _ in range(launches):
             fn()
-    for _ in range(3):
+    for _ in range(warm_replays):
         g.replay()
-    torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(replays):
@@ -436,7 +435,8 @@ def main():
     }
     if not args.only_headline:
         # one launch at a time (graph replay, no overlap between the tail of one launch and the head of the next)
-        line["us_in_graph"] = _graph_us(head.launch, launches=10, replays=10)
+        # (as many warm-up launches as the eager timing: the shader clock has to settle again after the idle gaps above)
+        line["us_in_graph"] = _graph_us(head.launch, launches=20, replays=25, warm_replays=15)
         ceil_tf = mfma_ceiling(gs, inputs, w.dtype)
         line["mfma_only_kernel_same_operand_distribution"] = {
             "tflops": ceil_tf, "frac_of_it": tflops / ceil_tf,
