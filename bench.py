@@ -40,7 +40,12 @@ def _algorithmic_bytes(w, gs_inputs, out_dtype="f32"):
     eo = 4 if out_dtype == "f32" else 2
     if isinstance(w, gs_inputs.GemmWorkload):
         return w.batch * (es * (w.M * w.K + w.K * w.N) + eo * w.M * w.N)
-    return es * (w.n * w.c * w.h * w.w + w.k * w.c * w.r * w.s) + eo * w.n * w.k * w.p * w.q
+    # convolution: only the input elements some window touches count (a stride larger than the filter skips rows and columns)
+    def touched(extent, out_extent, f):
+        hit = {o * w.stride - w.pad + t for o in range(out_extent) for t in range(f)}
+        return sum(1 for x in hit if 0 <= x < extent)
+    in_elems = w.n * w.c * touched(w.h, w.p, w.r) * touched(w.w, w.q, w.s)
+    return es * (in_elems + w.k * w.c * w.r * w.s) + eo * w.n * w.k * w.p * w.q
 
 
 COLD_BYTES = 640 << 20     # operand sets rotated through in the cold-cache timing (Infinity Cache: 256 MB)
