@@ -438,6 +438,15 @@ def main():
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": peak, "unit": "TFLOP/s",
                      "frac": tflops / peak, "traffic": traffic},
     }
+    prop = torch.cuda.get_device_properties(0)
+    ghz = prop.clock_rate / 1e6 if hasattr(prop, "clock_rate") else 2.4
+    line["device"] = {
+        "name": prop.name, "compute_units": prop.multi_processor_count, "clock_ghz": ghz,
+        # one 32x32x16 16-bit MFMA (32768 flop) per SIMD every 32 cycles, one 32x32x2 fp32 MFMA (4096 flop) every 64
+        "derived_peak_tflops": {"f16_bf16_mfma": prop.multi_processor_count * 4 * 1024 * ghz / 1e3,
+                                "f32_mfma": prop.multi_processor_count * 4 * 64 * ghz / 1e3},
+        "published_peaks_used": {"f16_bf16_mfma_tflops": PEAK_TFLOPS["f16"], "f32_mfma_tflops": PEAK_TFLOPS["f32"], "hbm_GBs": HBM_GBS},
+        "flop_convention": "GEMM 2MNK, BMM 2BMNK, conv 2 N K P Q C R S (padded taps counted)"}
     if not args.only_headline:
         # one launch at a time (graph replay, no overlap between the tail of one launch and the head of the next)
         # (as many warm-up launches as the eager timing: the shader clock has to settle again after the idle gaps above)
