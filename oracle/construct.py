@@ -508,10 +508,11 @@ def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, 
         return t
 
     t_pipe = max(t_mfma, t_lds, t_feed)
-    t_part = t_pipe * (nk_part / nk) / overlap + sync_time(nk_part)       # one part of a split tile
-    t_main = t_pipe / overlap + sync_time(nk)
+    share = min(resident, 2.0)      # a second resident workgroup works while the first waits at its k tile boundary
+    t_part = t_pipe * (nk_part / nk) / overlap + sync_time(nk_part) / share       # one part of a split tile
+    t_main = t_pipe / overlap + sync_time(nk) / share
     hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units
-    t_epi = bm * bn * eo / (0.8 * hbm_bw_cu)
+    t_epi = bm * bn * eo / (1.0 * hbm_bw_cu)      # write-through stores
     t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3
     # a second resident workgroup hides the stores of the first; further ones add nothing
     hide = min(resident, 2.0)

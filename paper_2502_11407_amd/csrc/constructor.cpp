@@ -380,10 +380,12 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
     if (stages == 1) t = t + (tiles_k - 1.0) * 4.0 * t_ktile;          // a single buffer: each further tile waits out its own fetch
     return t;
   };
-  const double t_part = t_main * (nk_part / nk) / overlap + sync_time(nk_part);     // one part of a split tile
-  t_main = t_main / overlap + sync_time(nk);
+  // (a second resident workgroup works while the first waits at its k tile boundary)
+  const double share = resident < 2.0 ? resident : 2.0;
+  const double t_part = t_main * (nk_part / nk) / overlap + sync_time(nk_part) / share;     // one part of a split tile
+  t_main = t_main / overlap + sync_time(nk) / share;
   const double hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units;
-  const double t_epi = bm * bn * eo / (0.8 * hbm_bw_cu);
+  const double t_epi = bm * bn * eo / (1.0 * hbm_bw_cu);      // write-through stores
   const double t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3;
   // a second resident workgroup hides the stores of the first; further ones add nothing
   const double hide = resident < 2.0 ? resident : 2.0;

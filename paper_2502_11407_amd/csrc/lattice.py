@@ -119,6 +119,11 @@ def lattice():
         for (bm, bn, bk, wm, wn, mb, vm, vn) in tiles32:
             out.append(_inst("f32", "f32", bm, bn, bk, wm, wn, mb, vm, vn, bsrc))
         out.append(_inst("f32", "f32", 64, 64, 16, 32, 32, 16, 1, 1, bsrc, vec=0))
+    # 128x128 tiles of eight 64x32 waves (two workgroups, sixteen waves per CU), direct staging: the mid-size
+    # shapes whose k loop waits on memory gain 3-6 % from the extra waves (appended last: ids above stay put)
+    for dt in ("f16", "bf16"):
+        for bsrc in ("KC", "NC"):
+            out.append(_inst(dt, "f32", 128, 128, 64, 64, 32, 32, 1, 1, bsrc, direct=1))
     for i, d in enumerate(out):
         d["id"] = i
     return out
