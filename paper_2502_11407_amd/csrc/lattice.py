@@ -124,6 +124,9 @@ def lattice():
     for dt in ("f16", "bf16"):
         for bsrc in ("KC", "NC"):
             out.append(_inst(dt, "f32", 128, 128, 64, 64, 32, 32, 1, 1, bsrc, direct=1))
+    for dt in ("f16", "bf16"):
+        for bsrc in ("KC", "NC"):
+            out.append(_inst(dt, dt, 128, 128, 64, 64, 32, 32, 1, 1, bsrc, direct=1))
     for i, d in enumerate(out):
         d["id"] = i
     return out
