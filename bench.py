@@ -329,6 +329,7 @@ def ablation(gs, inputs):
                 ("printed_keep_probability", gs.ConstructOpts(0, 0, 0, 1, 0, 0)),
                 ("footprint_ratio_inverted", gs.ConstructOpts(0, 0, 0, 0, 1, 0)),
                 ("one_walk", gs.ConstructOpts(0, 0, 1, 0, 0, 0)),
+                ("greedy_single_path", gs.ConstructOpts(0, 0, 1, 0, 0, 0, 0, 1)),
                 ("T0_1_as_literal", gs.ConstructOpts(1.0, 2.0 ** -100, 0, 0, 0, 0))]
     out = []
     cfgs = inputs.all_configs()

@@ -122,7 +122,8 @@ typedef struct {
   int32_t tiling_benefit;     /* 0: Eq. 1 as printed; 1: footprint ratio inverted (ablation) */
   int32_t no_vthread;         /* 1: setVThread disabled (ablation) */
   int32_t no_split_k;         /* 1: only split_k = 1 is ranked (callers without a workspace) */
-  int32_t reserved;
+  int32_t greedy;             /* 1: every step takes the action of largest benefit instead of drawing one
+                                 (a tree-like, single-path construction; ablation) */
 } gensor_construct_opts;
 
 /*

@@ -122,6 +122,7 @@ class Opts:
     tiling_benefit: int = 0
     no_vthread: int = 0
     no_split_k: int = 0
+    greedy: int = 0
 
 
 @dataclass
@@ -325,7 +326,10 @@ def roulette(probs: Sequence[float], u: float) -> int:
 
 def get_prog_policy(view: View, hw: Hw, opts: Opts, s: State, T_level: float, u: float) -> Tuple[int, int, List[float]]:
     probs = normalize(get_benefits(view, hw, opts, s, T_level))
-    i = roulette(probs, u)
+    if opts.greedy and any(p > 0.0 for p in probs):
+        i = max(range(len(probs)), key=lambda j: (probs[j], -j))      # first action of largest probability, no draw
+    else:
+        i = roulette(probs, u)
     if i < 0:
         return -1, -1, probs
     return ACTION_LIST[i][0], ACTION_LIST[i][1], probs

@@ -65,7 +65,7 @@ class Hw(C.Structure):
 class ConstructOpts(C.Structure):
     _fields_ = [("T0", C.c_double), ("threshold", C.c_double), ("chains", C.c_int32),
                 ("keep_policy", C.c_int32), ("tiling_benefit", C.c_int32), ("no_vthread", C.c_int32),
-                ("no_split_k", C.c_int32), ("reserved", C.c_int32)]
+                ("no_split_k", C.c_int32), ("greedy", C.c_int32)]
 
 
 class GensorError(RuntimeError):

@@ -87,6 +87,7 @@ void make_ctx(const GemmView& v, const gensor_hw* hw, const gensor_construct_opt
     d.tiling_benefit = o->tiling_benefit;
     d.no_vthread = o->no_vthread;
     d.no_split_k = o->no_split_k;
+    d.greedy = o->greedy;
   }
   c->opts = d;
   c->g = v.esize == 2 ? 16 : 8;
@@ -214,6 +215,12 @@ int prog_policy(const Ctx& c, const Etir& e, double T_level, double u, double pr
     return -1;
   }
   for (int i = 0; i < 9; ++i) probs[i] = probs[i] / total;
+  if (c.opts.greedy) {                       // the first action of largest probability, no draw
+    int top = 0;
+    for (int i = 1; i < 9; ++i)
+      if (probs[i] > probs[top]) top = i;
+    return top;
+  }
   double acc = 0.0;
   int last = -1;
   for (int i = 0; i < 9; ++i) {

@@ -302,7 +302,8 @@ def test_cpp_walk_equals_oracle_under_options():
     p, view = _views()[0]
     for (co, oo) in [(gs.ConstructOpts(0, 0, 0, 0, 1, 0), oc.Opts(tiling_benefit=1)),
                      (gs.ConstructOpts(0, 0, 0, 0, 0, 1), oc.Opts(no_vthread=1)),
-                     (gs.ConstructOpts(1.0, 2.0 ** -40, 0, 0, 0, 0), oc.Opts(T0=1.0, threshold=2.0 ** -40))]:
+                     (gs.ConstructOpts(1.0, 2.0 ** -40, 0, 0, 0, 0), oc.Opts(T0=1.0, threshold=2.0 ** -40)),
+                     (gs.ConstructOpts(0, 0, 0, 0, 0, 0, 0, 1), oc.Opts(greedy=1))]:
         for seed in range(4):
             a, d, st = gs.construct_trace(p, seed=seed, opts=co)
             w = oc.walk(view, HW, oo, seed, 0)
