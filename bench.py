@@ -162,15 +162,16 @@ def mfma_ceiling(gs, inputs, dtype, iters=20000):
     """TFLOP/s of a kernel of nothing but dense MFMAs whose operands are drawn like the headline's
     inputs (uniform [-1, 1)): the rate the chip's power limit allows for such values."""
     import torch
+    from paper_2502_11407_amd import probe
     vals = inputs.uniform_pm1(99, (128 * 1024,), dtype)                         # 256 KiB of operand fragments
     ops_dev = gs.to_device(vals, dtype)
     sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
     for _ in range(3):
-        gs.mfma_probe(dtype, ops_dev, sink, iters)
+        probe.mfma_probe(dtype, ops_dev, sink, iters, gs.hw_mi355x().compute_units)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    gs.mfma_probe(dtype, ops_dev, sink, iters)
+    probe.mfma_probe(dtype, ops_dev, sink, iters, gs.hw_mi355x().compute_units)
     e1.record()
     torch.cuda.synchronize()
     flops = gs.hw_mi355x().compute_units * 4.0 * iters * 8 * 2 * 32 * 32 * 16

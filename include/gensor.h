@@ -64,13 +64,18 @@ enum { GENSOR_DIM_M = 0, GENSOR_DIM_N = 1, GENSOR_DIM_K = 2 };
  * Conv2d m = filters k, n = (image, out row, out col), k = (channel, filter row, filter col).
  * tile[d][0] = T_2: workgroup tile staged in LDS       (BM, BN, BK)
  * tile[d][1] = T_1: wavefront tile held in registers   (WM, WN, and the MFMA k depth)
- * tile[d][2] = T_0: contiguous extent per virtual thread = tile[d][1] / vthread[d]
+ * tile[d][2] = T_0: extent per virtual thread = tile[d][1] / vthread[d]
+ * vthread[d]: virtual threads of Section IV-A / Eq. 3 on this hardware: the rows that one quarter
+ *   wave reads together from the LDS tile of the m (A) or n (B) operand are interleaved over
+ *   vthread[d] bank phases.  1 is the plain layout, whose reads conflict ceil(x / W) ways
+ *   (x = bytes of bank address space those rows span, W = 256 bytes served per cycle); at
+ *   vthread[d] = ceil(x / W) they are conflict-free, and that is the largest value on the lattice.
  */
 typedef struct {
   int32_t version;            /* GENSOR_SCHEDULE_VERSION */
   int32_t kernel_id;          /* index of the compiled instance; filled by gensor_construct */
   int32_t tile[3][3];
-  int32_t vthread[2];         /* V for m and n: the wave tile is split into V strided pieces */
+  int32_t vthread[2];         /* V for m and n: interleave depth of that operand's LDS tile (see above) */
   int32_t stages;             /* LDS buffers: 1, 2, or a ring of 3 (two k tiles in flight) */
   int32_t unroll;             /* MFMA k-steps unrolled per LDS stage = BK / (k per fragment) */
   int32_t vec_bytes;          /* width of one global access: 16, or the element size (scalar path) */
@@ -82,7 +87,8 @@ typedef struct {
   int32_t iterations;         /* walk steps per chain */
   int32_t chains;             /* independent walks */
   int32_t states_scored;      /* complete states handed to the cost model */
-  int32_t reserved;
+  int32_t round_units;        /* compute units a round of tiles is dealt over when split_k > 1: those of the hw the
+                                 schedule was constructed for (0: gensor_hw_mi355x()->compute_units) */
   uint64_t seed;
 } gensor_schedule;
 
@@ -162,7 +168,7 @@ gensor_status gensor_instance_schedule(int32_t id, const gensor_problem* p, gens
  * s == NULL: a schedule is constructed for `p` (seed 0) and remembered per shape.
  *
  * Split-k (s->split_k > 1).  Tiles are dealt to the compute units in rounds of
- * gensor_hw_mi355x()->compute_units.  The tiles of the last round, if it is not full (every
+ * s->round_units.  The tiles of the last round, if it is not full (every
  * tile when there are fewer tiles than units), are each computed by split_k workgroups,
  * every one over its own range of whole k tiles (needs ceil(K / BK) >= split_k, else
  * NO_SCHEDULE); the parts of a tile leave fp32 partial tiles in `workspace` and the part
@@ -244,19 +250,6 @@ gensor_status gensor_avgpool2d(gensor_dtype in_dtype, gensor_dtype out_dtype,
                                int64_t n, int64_t c, int64_t h, int64_t w, int64_t f, int64_t stride,
                                const void* input, void* output, void* hip_stream);
 
-/*
- * Measurement aid, not an operator: launches a kernel of nothing but dense 16-bit MFMAs
- * (one workgroup of 4 wavefronts per CU, 8 independent 32x32 accumulators per wavefront,
- * `iters` rounds of 8 instructions) whose A and B fragments are loaded once from
- * `operands` (device memory, 256 KiB, 16-byte aligned; the caller chooses the values).
- * The MFMA rate a chip sustains depends on the operand values through its power limit;
- * timing this launch with the operator's own input distribution gives the ceiling that
- * applies to it.  `sink` (device, 256 * 256 floats) receives one value per lane so the
- * work cannot be dropped.  in_dtype is GENSOR_F16 or GENSOR_BF16.  Flop count of one
- * launch: compute_units * 4 * iters * 8 * 2 * 32 * 32 * 16.
- */
-gensor_status gensor_mfma_probe(gensor_dtype in_dtype, const void* operands, float* sink,
-                                int32_t iters, void* hip_stream);
 const char* gensor_status_string(gensor_status st);
 
 #ifdef __cplusplus

@@ -1,9 +1,12 @@
-"""CPU oracle of the schedule constructor.  TEST INFRASTRUCTURE ONLY.
+"""CPU oracle of the schedule constructor's graph walk.  TEST INFRASTRUCTURE ONLY.
 
 The constructor is a stochastic heuristic, so this file follows the paper's algorithm step
 by step, in its notation, with the readings listed below for everything the paper leaves
 open.  It shares no code with the C++ constructor; both sides implement the same published
 counter-based generator (splitmix64 finaliser) so that a walk can be compared step by step.
+It covers what the paper defines: the state, the four actions, Eq. 1-3, Algorithms 1 and 2 and
+the states they keep.  It holds no cost model: how kept states are reduced to one program is
+the library's own design, pinned elsewhere (see "pick" below).
 
 Paper passages followed
   Section IV-A   state = ETIR: tiles per memory level, virtual threads, current level;
@@ -26,8 +29,12 @@ Readings (the paper is silent or garbled here)
              level 1: Q = e B_m B_n B_k (1/T_m + 1/T_n),       F = 4 T_m T_n + e T_k (T_m + T_n)
   Eq. 1      as printed: Q(T) F(T') / (Q(T') F(T)); option `tiling_benefit=1` inverts F
   Eq. 2      S = F of the current tile; L, B of the two levels from the hardware table, B per CU
-  Eq. 3      x = 16 T_1[d] bytes (a lane reads 16 bytes per fragment), W = banks x bank bytes;
-             setVThread cycles V 1 -> 2 -> 4 -> 1; benefit = ceil(x/(V W)) / ceil(x/(V' W))
+  Eq. 3      W = banks x bank bytes (what the LDS serves per cycle).  x = bytes of bank address space
+             spanned by the rows one quarter wave reads together from the operand tile of dimension d:
+             16 rows of min(T_2[k] e, W) bytes for a k-contiguous tile (A always, B when stored [n][k]),
+             else the 4 (16-bit) or 2 (fp32) k rows of an n-contiguous tile, W bytes each.  ceil(x/(V W))
+             of those rows share a bank when the tile is interleaved over V phases.  setVThread doubles V
+             up to ceil(x/W) (conflict-free) and then wraps to 1; benefit = ceil(x/(V W)) / ceil(x/(V' W))
   T, t       Algorithm 1 halves one temperature T per step and stops at the threshold.  The
              multiplier and the keep rule are both sigmoids centred at 10 in "-log T", so t is
              read as -log2 of a temperature.  Each memory level is annealed: the level
@@ -48,20 +55,18 @@ Readings (the paper is silent or garbled here)
              workgroup fits the wave limit is a complete program (stop there), so policy 0
              keeps each such visited state in its completed form; policy 1 keeps it with
              the printed probability 1 - 1/(1 + exp(-0.5 (-ln T - 10)))
-  pick       kept complete states are ranked by the analytical cost model below.  A state is
-             realised by every compiled instance on the same spatial tiles (T_2 and T_1 of m and
-             n: the sizes Eq. 1's traffic depends on); k tile, MFMA depth, V and staging mode are
-             then those of the instance.  The best such instance over all kept states wins (if
-             none exists, the instance nearest to the best-ranked state)
-  views      a pointwise convolution (1x1 filter, no padding) is walked and ranked as the
-             batched GEMM it is (one GEMM per image, n-contiguous B); other convolutions in
-             the implicit-GEMM view.  Instances that cache the input patch in LDS have a
-             cost model of their own (predict_patch_us: a serial chain per workgroup)
+  pick       how the kept states become one program is not part of the paper's algorithm and not of
+             this oracle: the library ranks the compiled instances that sit on a kept state's lattice
+             point with its own analytical cost model.  That model is product code; it is pinned by
+             measured launch times (tests/golden/instance_times.json) and by closed-form limits, and
+             the selection rule is re-derived in the tests from kept_states() below.
+  views      a pointwise convolution (1x1 filter, no padding) is walked as the batched GEMM it is
+             (one GEMM per image, n-contiguous B); other convolutions in the implicit-GEMM view
 """
 from __future__ import annotations
 
 import math
-from dataclasses import dataclass, field, replace
+from dataclasses import dataclass, field
 from typing import List, Optional, Sequence, Tuple
 
 M64 = (1 << 64) - 1
@@ -117,7 +122,7 @@ class Hw:
 class Opts:
     T0: float = 2.0 ** 30
     threshold: float = 2.0 ** -70
-    chains: int = 1024
+    chains: int = 4096
     keep_policy: int = 0
     tiling_benefit: int = 0
     no_vthread: int = 0
@@ -166,6 +171,16 @@ def mfma_block(view: View, s: State) -> int:
     return 32 if s.tile[DIM_K][1] == g_of(view) else 16
 
 
+def conflict_ways(view: View, hw: "Hw", bk: int, d: int, v: int) -> int:
+    """Eq. 3's ceil(x / (V W)) for the operand tile of dimension d (0: m x k, 1: k x n)."""
+    W = hw.lds_banks * hw.lds_bank_bytes
+    if d == DIM_M or view.bsrc == 0:
+        x = 16 * min(bk * view.e, W)
+    else:
+        x = (4 if view.e == 2 else 2) * W
+    return -(-x // (v * W))
+
+
 # ------------------------------------------------------------------ footprint / traffic
 def F(view: View, s: State, level: int) -> float:
     tm, tn, tk = s.tile[0][level], s.tile[1][level], s.tile[2][level]
@@ -199,11 +214,9 @@ def valid(view: View, hw: Hw, s: State) -> bool:
             return False
         mb = mfma_block(view, s)
         for d in (0, 1):
-            if s.v[d] not in (1, 2, 4):
+            if s.v[d] not in (1, 2, 4, 8, 16) or s.v[d] > conflict_ways(view, hw, s.tile[2][0], d, 1):
                 return False
-            if s.tile[d][1] > s.tile[d][0] or s.tile[d][1] < 16:
-                return False
-            if s.tile[d][1] % (mb * s.v[d]) != 0:
+            if s.tile[d][1] > s.tile[d][0] or s.tile[d][1] < 16 or s.tile[d][1] % mb != 0:
                 return False
         regs = s.tile[0][1] * s.tile[1][1] // 64 + 2 * (s.tile[0][1] + s.tile[1][1]) * s.tile[2][1] * view.e // 256
         if regs > hw.regs_per_lane:
@@ -215,7 +228,7 @@ def waves(s: State) -> int:
     return (s.tile[0][0] // s.tile[0][1]) * (s.tile[1][0] // s.tile[1][1])
 
 
-def apply_action(view: View, s: State, ac: int, d: int) -> State:
+def apply_action(view: View, hw: "Hw", s: State, ac: int, d: int) -> State:
     """applyProgPolicy: the state after action `ac` on dimension `d` (no legality check)."""
     n = s.copy()
     if ac == TILE:
@@ -223,9 +236,8 @@ def apply_action(view: View, s: State, ac: int, d: int) -> State:
     elif ac == INVTILE:
         n.tile[d][s.level] //= 2
     elif ac == SETVTHREAD:
-        mb = mfma_block(view, s)
         nv = s.v[d] * 2
-        if nv > 4 or s.tile[d][1] % (mb * nv) != 0:
+        if nv > conflict_ways(view, hw, s.tile[2][0], d, 1):
             nv = 1
         n.v[d] = nv
     elif ac == CACHE:
@@ -235,7 +247,7 @@ def apply_action(view: View, s: State, ac: int, d: int) -> State:
             n.tile[0][1], n.tile[1][1], n.tile[2][1] = 16, 16, 2 * g
     if n.level >= 1:
         for dd in (0, 1):
-            n.tile[dd][2] = n.tile[dd][1] // n.v[dd]
+            n.tile[dd][2] = max(1, n.tile[dd][1] // n.v[dd])
         n.tile[2][2] = n.tile[2][1]
     return n
 
@@ -257,10 +269,9 @@ def benefit_caching(view: View, hw: Hw, s: State) -> float:
     return (hw.latency_ns[lo] + S / b_lo) / (hw.latency_ns[hi] + S / b_hi)
 
 
-def benefit_vthread(hw: Hw, s: State, n: State, d: int) -> float:
-    x = 16.0 * s.tile[d][1]
-    W = float(hw.lds_banks * hw.lds_bank_bytes)
-    return math.ceil(x / (s.v[d] * W)) / math.ceil(x / (n.v[d] * W))
+def benefit_vthread(view: View, hw: Hw, s: State, n: State, d: int) -> float:
+    bk = s.tile[2][0]
+    return conflict_ways(view, hw, bk, d, s.v[d]) / conflict_ways(view, hw, bk, d, n.v[d])
 
 
 def annealing_factor(t: float) -> float:
@@ -285,14 +296,14 @@ def get_benefits(view: View, hw: Hw, opts: Opts, s: State, T_level: float) -> Li
     for (ac, d) in ACTION_LIST:
         b = 0.0
         if ac in (TILE, INVTILE):
-            n = apply_action(view, s, ac, d)
+            n = apply_action(view, hw, s, ac, d)
             if valid(view, hw, n):
                 b = benefit_tiling(view, s, n, opts)
         elif ac == SETVTHREAD:
             if s.level == 1 and not opts.no_vthread:
-                n = apply_action(view, s, ac, d)
+                n = apply_action(view, hw, s, ac, d)
                 if n.v[d] != s.v[d] and valid(view, hw, n):
-                    b = benefit_vthread(hw, s, n, d)
+                    b = benefit_vthread(view, hw, s, n, d)
         else:
             ok = True
             if s.level == 1 and waves(s) > hw.max_waves_per_wg:
@@ -355,13 +366,13 @@ def walk(view: View, hw: Hw, opts: Opts, seed: int, chain: int = 0) -> Walk:
         ac, d, _ = get_prog_policy(view, hw, opts, e, T_level, uniform(seed, chain, step, 0))
         if ac < 0:
             break
-        e2 = apply_action(view, e, ac, d)
+        e2 = apply_action(view, hw, e, ac, d)
         out.actions.append(ac)
         out.dims.append(d)
         out.states.append(e2.flat())
         if e2.level == 2 or (e2.level == 1 and waves(e2) <= hw.max_waves_per_wg):
             if opts.keep_policy == 0 or uniform(seed, chain, step, 1) < keep_probability(T):
-                out.kept.append(e2 if e2.level == 2 else apply_action(view, e2, CACHE, -1))
+                out.kept.append(e2 if e2.level == 2 else apply_action(view, hw, e2, CACHE, -1))
         e = e2
         T = T / 2.0
         T_level = T0 if ac == CACHE else T_level / 2.0
@@ -369,220 +380,17 @@ def walk(view: View, hw: Hw, opts: Opts, seed: int, chain: int = 0) -> Walk:
     return out
 
 
-# ------------------------------------------------------------------ cost model and pick
-@dataclass
-class Instance:
-    id: int
-    bm: int
-    bn: int
-    bk: int
-    wm: int
-    wn: int
-    kg: int
-    vm: int
-    vn: int
-    vec: int
-    stages: int
-    direct: int
-    split_ok: int = 0      # also compiled with split tiles
-    split: int = 1         # split factor of a pick
-
-
-def predict_patch_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, stages) -> float:
-    """Patch-staged convolution: every workgroup runs a serial chain (first fetch, then per
-    channel stage: fetch issue, taps x MFMA, transpose + LDS commit, barriers; then the
-    stores); workgroups beyond the resident ones queue behind it."""
-    e, eo = view.e, view.e_out
-    n, c, h, w, r, s, stride, pad = view.conv
-    g = 16 if e == 2 else 8
-    mb = 32 if kg == g else 16
-    epc = 16 // e
-    P = (h + 2 * pad - r) // stride + 1
-    Qo = (w + 2 * pad - s) // stride + 1
-    RS = r * s
-    nst = math.ceil(c / bk)
-    out_rows = min(math.ceil((bn - 1) / Qo) + 1, n * P)
-    rows = (out_rows - 1) * stride + r + 2 * pad
-    pw = w + 2 * pad
-    stage = bm * (RS * bk * e + 16) + rows * pw * (bk * e + 16)
-    lds = stages * stage + (0 if RS in (1, 9) else bm * RS * bk * e)        # + the raw filter runs
-    if lds > hw.lds_bytes_per_cu:
-        return -1.0
-    nwaves = (bm // wm) * (bn // wn)
-    if nwaves > hw.max_waves_per_wg:
-        return -1.0
-    units = math.ceil(rows * math.ceil(w / epc) * (bk // epc) / (nwaves * 64))
-    avec = math.ceil(bm * RS * bk / epc / (nwaves * 64))
-    regs = wm * wn // 64 + (wm + wn) // 2 + 32 * units + 4 * avec + 48
-    if regs > hw.regs_per_lane:
-        return -1.0
-    occ = min(hw.lds_bytes_per_cu // lds, (hw.simds_per_cu * (hw.regs_per_lane // regs)) // nwaves, 8)
-    if occ < 1:
-        return -1.0
-    tiles = math.ceil(view.M / bm) * math.ceil(view.N / bn)
-    resident = min(occ, math.ceil(tiles / hw.compute_units))
-    rounds = max(1.0, tiles / (hw.compute_units * occ))
-    share = max(1.0, resident * nwaves / hw.simds_per_cu)
-    peak_simd = (hw.mfma_tflops_16bit if e == 2 else hw.mfma_tflops_f32) * 1e6 / (hw.compute_units * hw.simds_per_cu)
-    ksteps = bk // kg
-    t_mfma = RS * ksteps * (wm // mb) * (wn // mb) * (2.0 * mb * mb * kg) / peak_simd * share
-    lds_bw = hw.bandwidth_gbs[1] * 1e3 / hw.compute_units
-    t_lds = RS * ksteps * ((wm // mb) + (wn // mb)) * 1024.0 * nwaves / lds_bw * resident
-    l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units
-    t_feed = (rows * w * bk * e + bm * RS * bk * e) / (0.5 * l2_bw)      # 16-byte gathers: half the L2 rate; hidden by the other resident workgroups
-    t_fixed = (0.75 * hw.latency_ns[0] + 1.5 * hw.latency_ns[1]) * 1e-3     # fetch issue, commit, two barriers
-    t_stage = t_mfma + t_lds + t_feed + t_fixed
-    t_pro = (2.0 * hw.latency_ns[0] + 6.0 * hw.latency_ns[1]) * 1e-3        # index set-up, first fetch at full latency, zero fill
-    t_epi = bm * bn * eo / (0.6 * hw.bandwidth_gbs[0] * 1e3 / hw.compute_units)
-    t_cu = rounds * (t_pro + nst * t_stage + t_epi)
-    bytes_total = e * (n * c * h * w + view.M * view.K) + eo * view.M * view.N
-    t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3)
-    return max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + hw.launch_us
-
-
-SPLITS = (1, 2, 3, 4, 6, 8, 12, 16)      # split factors the ranking tries on every candidate instance
-
-
-def predict_us(view: View, hw: Hw, bm, bn, bk, wm, wn, kg, vm, vn, vec, stages, direct, split=1) -> float:
-    """Analytical time of one launch: per-CU pipeline limits (MFMA, LDS, L2 feed) scaled by
-    how many tiles the busiest CU owns, an epilogue that streams C, bounded below by HBM.
-    split > 1: the tiles that do not fill a whole round of compute units (all of them when there are
-    fewer tiles than units) are computed by `split` workgroups each over 1/split of the k tiles; the
-    parts exchange fp32 partial tiles through device memory (a quarter of the HBM rate) and a dependent
-    launch clears their arrival counters first.  Infeasible if there is nothing to split."""
-    if view.bsrc == 2 and direct and view.conv is not None:
-        return predict_patch_us(view, hw, bm, bn, bk, wm, wn, kg, stages) if split == 1 else -1.0
-    if split < 1 or (split > 1 and view.bsrc not in (0, 1)):
-        return -1.0
-    e, eo = view.e, view.e_out
-    g = 16 if e == 2 else 8
-    mb = 32 if kg == g else 16
-    tiles_m = math.ceil(view.M / bm)
-    tiles_n = math.ceil(view.N / bn)
-    tiles = tiles_m * tiles_n * view.batch
-    nwaves = (bm // wm) * (bn // wn)
-    if nwaves > hw.max_waves_per_wg:
-        return -1.0
-    lds = stages * e * bk * (bm + bn)
-    if lds > hw.lds_bytes_per_cu:
-        return -1.0
-    regs = wm * wn // 64 + 2 * (wm + wn) * kg * e // 256 + (0 if direct else (e * bk * (bm + bn)) // (nwaves * 64 * 4)) + 32
-    if regs > hw.regs_per_lane:
-        return -1.0
-    waves_per_simd = min(8, hw.regs_per_lane // regs)
-    occ = min(hw.lds_bytes_per_cu // lds, (hw.simds_per_cu * waves_per_simd) // nwaves, 8)
-    if occ < 1:
-        return -1.0
-    nk = float(math.ceil(view.K / bk))
-    whole, nk_part = float(tiles), nk
-    if split > 1:
-        whole = float(math.floor(tiles / hw.compute_units) * hw.compute_units)
-        if whole == tiles or nk < split:
-            return -1.0
-        nk_part = float(math.ceil(nk / split))
-    cu_whole = float(math.ceil(whole / hw.compute_units))
-    cu_part = float(math.ceil((tiles - whole) * split / hw.compute_units))
-    cu_tiles = cu_whole + cu_part
-    resident = min(float(occ), cu_tiles)
-    kp = nk * bk
-    peak = (hw.mfma_tflops_16bit if e == 2 else hw.mfma_tflops_f32) * 1e6 / hw.compute_units   # flop/us per CU
-    simd_use = min(1.0, nwaves * resident / hw.simds_per_cu)
-    t_mfma = 2.0 * bm * bn * kp / (peak * simd_use * (1.0 if mb == 32 else 0.9))
-    lds_bw = hw.bandwidth_gbs[1] * 1e3 / hw.compute_units                                     # bytes/us per CU
-    t_lds = e * kp * (bm * (bn // wn) + bn * (bm // wm) + (bm + bn)) / lds_bw
-    l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units
-    gather = 16.0 if (view.bsrc == 2 and not direct) else 1.0     # element-wise loads and their index arithmetic
-    scalar = 1.0 if vec else 6.0
-    t_feed = scalar * e * kp * (bm + gather * bn) / l2_bw
-    overlap = 0.7 + 0.1 * min(resident * nwaves / hw.simds_per_cu, 3.0)
-    if direct and view.bsrc == 0:          # measured: direct staging pays for k-contiguous operands only
-        overlap += 0.05
-    if direct and view.bsrc == 0 and stages == 2 and wm * wn >= 128 * 128 and bk == 4 * kg:   # the two-steps-ahead schedule of the one-wave-per-SIMD tiles (k-contiguous operands: measured)
-        overlap += 0.12
-    # every k tile boundary (barrier, refill of the fragment pipeline) exposes a share of the memory latency
-    # (a ring of three and more stages keeps more tiles in flight; measured to pay for k-contiguous operands)
-    t_ktile = 0.25 * hw.latency_ns[0] * 1e-3
-
-    def sync_time(tiles_k: float) -> float:
-        t = tiles_k * t_ktile
-        if stages > 2 and view.bsrc == 0:
-            t = t / (stages - 1)
-        if stages == 1:
-            t = t + (tiles_k - 1.0) * 4.0 * t_ktile        # a single buffer: each further tile waits out its own fetch
-        return t
-
-    t_pipe = max(t_mfma, t_lds, t_feed)
-    share = min(resident, 2.0)      # a second resident workgroup works while the first waits at its k tile boundary
-    t_part = t_pipe * (nk_part / nk) / overlap + sync_time(nk_part) / share       # one part of a split tile
-    t_main = t_pipe / overlap + sync_time(nk) / share
-    hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units
-    t_epi = bm * bn * eo / (1.0 * hbm_bw_cu)      # write-through stores
-    t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3
-    # a second resident workgroup hides the stores of the first; further ones add nothing
-    hide = min(resident, 2.0)
-    # a part writes its partial tile, and one part in `split` reads the others' and stores C
-    t_swap = bm * bn * 4.0 / (0.8 * hbm_bw_cu)
-    t_cu = cu_whole * (t_main + t_epi / hide) + cu_part * (t_part + t_swap + (t_swap * (split - 1) + t_epi) / split / hide) + t_fill
-    bytes_total = view.batch * (e * (view.M * view.K + view.K * view.N) + eo * view.M * view.N)
-    bytes_swap = (tiles - whole) * (2.0 * split - 1.0) * bm * bn * 4.0 if split > 1 else 0.0
-    t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3) + bytes_swap / (0.25 * hw.bandwidth_gbs[0] * 1e3)
-    # soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)
-    return (max(t_cu, t_hbm) + 0.3 * min(t_cu, t_hbm) + hw.launch_us * (3.5 if view.prepass else 1.0)
-            + (hw.launch_us if split > 1 else 0.0))
-
-
-def pick(view: View, hw: Hw, kept: Sequence[State], instances: Sequence[Instance], vec_ok: bool,
-         no_split_k: int = 0) -> Tuple[Optional[Instance], float, int]:
-    """Rank kept complete states by the cost model; return the best compiled instance."""
-    best, best_us, scored = None, 0.0, 0
-    seen = set()
-    ranked = []
-    for s in kept:
-        key = tuple(s.flat())
-        if key in seen:
-            continue
-        seen.add(key)
-        bm, bn, bk = s.tile[0][0], s.tile[1][0], s.tile[2][0]
-        wm, wn, kg = s.tile[0][1], s.tile[1][1], s.tile[2][1]
-        scored += 1
-        # every compiled instance on the same spatial tiles (T_2 and T_1 of m and n) realises the
-        # state; its k tile, MFMA depth, V and staging mode are whatever was compiled
-        for i in instances:
-            if (i.bm, i.bn, i.wm, i.wn) != (bm, bn, wm, wn) or (i.vec and not vec_ok):
-                continue
-            if i.direct and view.bsrc != 2 and view.K % i.bk != 0:
-                continue
-            for split in SPLITS:
-                if split > 1 and (no_split_k or not i.split_ok):
-                    break
-                us = predict_us(view, hw, i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn, i.vec, i.stages, i.direct, split)
-                if us > 0 and (best is None or us < best_us):
-                    best, best_us = replace(i, split=split), us
-        us0 = predict_us(view, hw, bm, bn, bk, wm, wn, kg, s.v[0], s.v[1], 1 if vec_ok else 0, 2, 0)
-        if us0 > 0:
-            ranked.append((us0, s))
-    if best is None and ranked:
-        us0, s = min(ranked, key=lambda r: r[0])
-        target = [s.tile[0][0], s.tile[1][0], s.tile[2][0], s.tile[0][1], s.tile[1][1], s.tile[2][1], s.v[0], s.v[1]]
-        bd = None
-        for i in instances:
-            if (i.vec and not vec_ok) or (i.direct and view.bsrc != 2 and view.K % i.bk != 0):
-                continue
-            us = predict_us(view, hw, i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn, i.vec, i.stages, i.direct)
-            if us <= 0:
-                continue
-            cand = [i.bm, i.bn, i.bk, i.wm, i.wn, i.kg, i.vm, i.vn]
-            dist = sum(abs(math.log2(a) - math.log2(b)) for a, b in zip(cand, target))
-            if bd is None or dist < bd or (dist == bd and us < best_us):
-                bd, best, best_us = dist, i, us
-    return best, best_us, scored
-
-
-def construct(view: View, hw: Hw, opts: Opts, seed: int, instances: Sequence[Instance], vec_ok: bool = True):
-    kept: List[State] = []
+def kept_states(view: View, hw: Hw, opts: Opts, seed: int) -> List[Tuple[int, ...]]:
+    """The distinct complete states (State.flat()) that Algorithm 1's top_results holds after all walks,
+    in order of first appearance."""
+    seen, out = set(), []
     for chain in range(opts.chains):
-        kept.extend(walk(view, hw, opts, seed, chain).kept)
-    return pick(view, hw, kept, instances, vec_ok, opts.no_split_k)
+        for s in walk(view, hw, opts, seed, chain).kept:
+            key = tuple(s.flat())
+            if key not in seen:
+                seen.add(key)
+                out.append(key)
+    return out
 
 
 def transition_row(view: View, hw: Hw, opts: Opts, s: State, T_level: float) -> List[float]:

@@ -23,7 +23,7 @@ OP_GEMM, OP_BMM, OP_CONV2D = 0, 1, 2
 
 EXPORTS = ["gensor_hw_mi355x", "gensor_construct", "gensor_construct_trace", "gensor_predict_us",
            "gensor_num_instances", "gensor_instance_schedule", "gensor_gemm", "gensor_bmm", "gensor_conv2d",
-           "gensor_workspace_bytes", "gensor_status_string", "gensor_mfma_probe", "gensor_gemv", "gensor_avgpool2d"]
+           "gensor_workspace_bytes", "gensor_status_string", "gensor_gemv", "gensor_avgpool2d"]
 
 
 class Problem(C.Structure):
@@ -42,7 +42,7 @@ class Schedule(C.Structure):
                 ("direct_lds", C.c_int32), ("split_k", C.c_int32), ("wg_remap", C.c_int32),
                 ("predicted_us", C.c_double), ("construct_s", C.c_double),
                 ("iterations", C.c_int32), ("chains", C.c_int32), ("states_scored", C.c_int32),
-                ("reserved", C.c_int32), ("seed", C.c_uint64)]
+                ("round_units", C.c_int32), ("seed", C.c_uint64)]
 
     def describe(self) -> dict:
         t = [[self.tile[d][l] for l in range(3)] for d in range(3)]
@@ -106,8 +106,6 @@ def _load():
     L.gensor_gemv.argtypes = [i32, i64, i64, f32, vp, i64, vp, f32, vp, vp]
     L.gensor_avgpool2d.restype = i32
     L.gensor_avgpool2d.argtypes = [i32, i32, i64, i64, i64, i64, i64, i64, vp, vp, vp]
-    L.gensor_mfma_probe.restype = i32
-    L.gensor_mfma_probe.argtypes = [i32, vp, vp, i32, vp]
     return L
 
 
@@ -260,13 +258,6 @@ def avgpool2d(dtype: str, I, O, f: int, stride: int, out_dtype: str = "f32", str
     st = lib.gensor_avgpool2d(DTYPE[dtype], DTYPE[out_dtype], n, c, h, w, f, stride, I.data_ptr(), O.data_ptr(),
                               _stream_ptr(stream))
     _check(st, "gensor_avgpool2d")
-
-
-def mfma_probe(dtype: str, operands, sink, iters: int, stream=None):
-    """Launch the MFMA-only probe kernel (measurement aid): `operands` is a 256 KiB device tensor whose
-    values are the A and B fragments, `sink` a device tensor of 65536 floats."""
-    st = lib.gensor_mfma_probe(DTYPE[dtype], operands.data_ptr(), sink.data_ptr(), iters, _stream_ptr(stream))
-    _check(st, "gensor_mfma_probe")
 
 
 def gemm_workspace(p: Problem, schedule: Schedule):

@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 PKG = os.path.dirname(HERE)
 GEN = os.path.join(HERE, "_build")
 LIB = os.path.join(PKG, "libgensor.so")
+PROBE_LIB = os.path.join(PKG, "libgensor_probe.so")     # the benchmark's MFMA-only probe, a library of its own
 sys.path.insert(0, HERE)
 import lattice  # noqa: E402
 
@@ -65,7 +66,7 @@ def generate():
         es = 4 if d["dt"] == "f32" else 2
         kg = (64 // d["mb"]) * (16 // es)
         a_bytes = d["bm"] * d["bk"] * es
-        b_bytes = d["bn"] * d["bk"] * es if (d["bsrc"] == "KC" or d["direct"]) else d["bk"] * (d["bn"] * es + 32)
+        b_bytes = d["bn"] * d["bk"] * es if (d["bsrc"] == "KC" or d["direct"]) else d["bk"] * (d["bn"] * es + lattice.pad_n(d))
         lds = 0 if d["units"] else (a_bytes + b_bytes) * d["stages"]
         threads = (d["bm"] // d["wm"]) * (d["bn"] // d["wn"]) * 64
         reg.append("  {%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, launch_%d, %s}," % (
@@ -105,16 +106,17 @@ def _compile(src):
 
 def build(force=False, jobs=None):
     tus = generate()
-    tus += [os.path.join(HERE, "gensor_api.cpp"), os.path.join(HERE, "constructor.cpp"), os.path.join(HERE, "probe.cpp"), os.path.join(HERE, "scan_kernels.cpp")]
+    tus += [os.path.join(HERE, "gensor_api.cpp"), os.path.join(HERE, "constructor.cpp"), os.path.join(HERE, "scan_kernels.cpp")]
+    probe = os.path.join(HERE, "probe.cpp")
     if force:
         for f in os.listdir(GEN):
             if f.endswith(".o"):
                 os.remove(os.path.join(GEN, f))
     jobs = jobs or min(8, os.cpu_count() or 1)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(_compile, tus))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
-    subprocess.run(cmd, check=True)
+        objs = list(ex.map(_compile, tus + [probe]))
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs[:-1], check=True)
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROBE_LIB, objs[-1]], check=True)
     return LIB
 
 

@@ -3,16 +3,22 @@
 // ranks the complete states the walks end in and returns the best compiled instance.
 //
 // State (Section IV-A): tile[d] = [T_2, T_1, T_0] for d = m, n, k of the GEMM view, the
-// virtual-thread split V for m and n, and the memory level being scheduled
-// (0: T_2 / LDS, 1: T_1 / registers, 2: complete).  Actions: tile (double), invTile
-// (halve), setVThread (V cycles 1 -> 2 -> 4 -> 1), cache (next level).
+// virtual threads V for m and n (interleave depth of that operand's LDS tile), and the memory
+// level being scheduled (0: T_2 / LDS, 1: T_1 / registers, 2: complete).  Actions: tile
+// (double), invTile (halve), setVThread (V doubles, wrapping to 1 past the conflict-free
+// depth), cache (next level).
 //
 // Where the paper leaves a quantity open this file takes these readings:
 //   * Q and F of Eq. 1 -- level 0: Q = e M N K (1/T_m + 1/T_n) + e_out M N, F = e T_k (T_m + T_n);
 //     level 1: Q = e B_m B_n B_k (1/T_m + 1/T_n), F = 4 T_m T_n + e T_k (T_m + T_n).
 //   * Eq. 2 -- S is F of the current tile; L and B come from gensor_hw, B shared per CU.
-//   * Eq. 3 -- x = 16 T_1[d] bytes, W = banks * bank bytes; the ratio is taken between the
-//     old and the new V so that the wrap 4 -> 1 has a (small) positive benefit.
+//   * Eq. 3 -- W = banks * bank bytes, what the LDS serves per cycle.  x = the bytes of bank address
+//     space spanned by the rows that one quarter wave reads together from the operand tile of
+//     dimension d: 16 rows of min(T_2[k] e, W) bytes for a k-contiguous tile, the 4 (16-bit) or 2
+//     (fp32) k rows of an n-contiguous tile at W each.  ceil(x / (V W)) of those rows share a bank
+//     when the tile is interleaved over V phases (V = 1: the plain layout).  setVThread doubles V
+//     up to ceil(x / W), where the reads are conflict-free, then wraps to 1; the benefit is the
+//     ratio of the conflict ways before and after, so the wrap has a (small) positive benefit.
 //   * The cache entry is multiplied by 3 / (1 + exp(-(ln 5 / 10)(t - 10))) with
 //     t = -log2(T_l); T_l is a per-level temperature that starts at T0, halves each step
 //     and restarts when cache fires.  The loop's own T halves each step and ends the walk.
@@ -78,7 +84,7 @@ int next_pow2(int64_t x) {
 void make_ctx(const GemmView& v, const gensor_hw* hw, const gensor_construct_opts* o, Ctx* c) {
   c->view = v;
   c->hw = hw ? *hw : kMi355x;
-  gensor_construct_opts d = {std::ldexp(1.0, 30), std::ldexp(1.0, -70), 1024, 0, 0, 0, 0, 0};
+  gensor_construct_opts d = {std::ldexp(1.0, 30), std::ldexp(1.0, -70), 4096, 0, 0, 0, 0, 0};
   if (o) {
     if (o->T0 > 0) d.T0 = o->T0;
     if (o->threshold > 0) d.threshold = o->threshold;
@@ -108,6 +114,16 @@ Etir initial_state(const Ctx& c) {
 }
 
 int mfma_block(const Ctx& c, const Etir& e) { return e.tile[2][1] == c.g ? 32 : 16; }
+
+// Eq. 3: bank-conflict ways of the fragment reads of operand d (0: the m x k tile, 1: the k x n tile)
+// of a workgroup tile of k depth bk whose rows are interleaved over v phases.
+int conflict_ways(const GemmView& view, const gensor_hw& hw, int bk, int d, int v) {
+  const int W = hw.lds_banks * hw.lds_bank_bytes;
+  const bool k_contiguous = d == 0 || view.bsrc == B_KC;
+  const int row_bytes = bk * view.esize;
+  const int x = k_contiguous ? 16 * (row_bytes < W ? row_bytes : W) : (view.esize == 2 ? 4 : 2) * W;
+  return (x + v * W - 1) / (v * W);
+}
 int wave_count(const Etir& e) { return (e.tile[0][0] / e.tile[0][1]) * (e.tile[1][0] / e.tile[1][1]); }
 
 // memory footprint F and traffic Q of Eq. 1 at a level
@@ -134,9 +150,8 @@ bool valid(const Ctx& c, const Etir& e) {
     if ((e.tile[2][1] != c.g && e.tile[2][1] != 2 * c.g) || e.tile[2][1] > e.tile[2][0]) return false;
     const int mb = mfma_block(c, e);
     for (int d = 0; d < 2; ++d) {
-      if (e.v[d] != 1 && e.v[d] != 2 && e.v[d] != 4) return false;
-      if (e.tile[d][1] > e.tile[d][0] || e.tile[d][1] < 16) return false;
-      if (e.tile[d][1] % (mb * e.v[d]) != 0) return false;
+      if (e.v[d] < 1 || (e.v[d] & (e.v[d] - 1)) != 0 || e.v[d] > conflict_ways(c.view, c.hw, e.tile[2][0], d, 1)) return false;
+      if (e.tile[d][1] > e.tile[d][0] || e.tile[d][1] < 16 || e.tile[d][1] % mb != 0) return false;
     }
     const int regs = e.tile[0][1] * e.tile[1][1] / 64 + 2 * (e.tile[0][1] + e.tile[1][1]) * e.tile[2][1] * c.view.esize / 256;
     if (regs > c.hw.regs_per_lane) return false;
@@ -151,7 +166,7 @@ Etir apply_action(const Ctx& c, const Etir& e, int action, int d) {
     case ACT_INVTILE: n.tile[d][e.level] /= 2; break;
     case ACT_SETVTHREAD: {
       int nv = e.v[d] * 2;
-      if (nv > 4 || e.tile[d][1] % (mfma_block(c, e) * nv) != 0) nv = 1;
+      if (nv > conflict_ways(c.view, c.hw, e.tile[2][0], d, 1)) nv = 1;
       n.v[d] = nv;
       break;
     }
@@ -161,8 +176,8 @@ Etir apply_action(const Ctx& c, const Etir& e, int action, int d) {
       break;
   }
   if (n.level >= 1) {
-    n.tile[0][2] = n.tile[0][1] / n.v[0];
-    n.tile[1][2] = n.tile[1][1] / n.v[1];
+    n.tile[0][2] = n.tile[0][1] / n.v[0] > 0 ? n.tile[0][1] / n.v[0] : 1;
+    n.tile[1][2] = n.tile[1][1] / n.v[1] > 0 ? n.tile[1][1] / n.v[1] : 1;
     n.tile[2][2] = n.tile[2][1];
   }
   return n;
@@ -182,9 +197,7 @@ double benefit_caching(const Ctx& c, const Etir& e) {                      // Eq
   return (c.hw.latency_ns[lo] + S / b_lo) / (c.hw.latency_ns[hi] + S / b_hi);
 }
 double benefit_vthread(const Ctx& c, const Etir& e, const Etir& n, int d) {  // Eq. 3
-  const double x = 16.0 * e.tile[d][1];
-  const double W = (double)(c.hw.lds_banks * c.hw.lds_bank_bytes);
-  return std::ceil(x / (e.v[d] * W)) / std::ceil(x / (n.v[d] * W));
+  return (double)conflict_ways(c.view, c.hw, e.tile[2][0], d, e.v[d]) / (double)conflict_ways(c.view, c.hw, e.tile[2][0], d, n.v[d]);
 }
 double annealing_factor(double t) { return 3.0 / (1.0 + std::exp(-(std::log(5.0) / 10.0) * (t - 10.0))); }
 double keep_probability(double T) { return 1.0 - 1.0 / (1.0 + std::exp(-0.5 * (-std::log(T) - 10.0))); }
@@ -328,9 +341,9 @@ double predict_patch(const GemmView& v, const gensor_hw& hw, int bm, int bn, int
 // dependent launch clears their arrival counters first.  Infeasible if there is nothing to split.
 double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, int wm, int wn, int kg,
                int vm, int vn, int vec, int stages, int direct, int split) {
-  (void)vm; (void)vn;
   if (v.bsrc == B_CONV && direct) return split == 1 ? predict_patch(v, hw, bm, bn, bk, wm, wn, kg, stages) : -1.0;
   if (split < 1 || (split > 1 && v.bsrc != B_KC && v.bsrc != B_NC)) return -1.0;
+  if (vm < 1 || vn < 1 || bm < 1 || bn < 1 || bk < 1 || wm < 1 || wn < 1 || kg < 1 || stages < 1) return -1.0;
   const int e = v.esize, eo = v.osize;
   const int g = e == 2 ? 16 : 8;
   const int mb = kg == g ? 32 : 16;
@@ -365,7 +378,9 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   if (simd_use > 1.0) simd_use = 1.0;
   const double t_mfma = 2.0 * bm * bn * kp / (peak * simd_use * (mb == 32 ? 1.0 : 0.9));
   const double lds_bw = hw.bandwidth_gbs[1] * 1e3 / hw.compute_units;
-  const double t_lds = e * kp * (bm * (bn / wn) + bn * (bm / wm) + (bm + bn)) / lds_bw;
+  // fragment reads of the two operand tiles, each slowed by its bank-conflict ways (Eq. 3), and the tile's deposit
+  const double t_lds = e * kp * ((double)bm * (bn / wn) * conflict_ways(v, hw, bk, 0, vm) +
+                                 (double)bn * (bm / wm) * conflict_ways(v, hw, bk, 1, vn) + (bm + bn)) / lds_bw;
   const double l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units;
   const double gather = (v.bsrc == B_CONV && !direct) ? 16.0 : 1.0;     // element-wise loads and their index arithmetic
   const double scalar = vec ? 1.0 : 6.0;
@@ -452,16 +467,20 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
   for (const Etir& e : kept) {
     if (!seen.insert(e).second) continue;
     ++scored;
-    // every compiled instance on the same spatial tiles (T_2 and T_1 of m and n) realises the
-    // state; its k tile, MFMA depth, V and staging mode are whatever was compiled
+    // a compiled instance realises the state if it sits on the same lattice point: T_2 and T_1 of m, n
+    // and k, and both V.  What the walk does not decide (LDS stages, direct staging, vector width) is
+    // whatever was compiled.  A patch-staged convolution instance has a k order and an LDS layout of its own
+    // (channels per stage, the halo patch), so only its spatial tiles are compared.
     for (int i = 0; i < g_num_instances; ++i) {
       const InstanceDesc& d = g_instances[i];
       if (d.bm != e.tile[0][0] || d.bn != e.tile[1][0] || d.wm != e.tile[0][1] || d.wn != e.tile[1][1]) continue;
+      if (!d.units && (d.bk != e.tile[2][0] || d.kg != e.tile[2][1] || d.vm != e.v[0] || d.vn != e.v[1])) continue;
       if (!usable(d, v, vec_ok)) continue;
       for (int split : kSplits) {
         if (split > 1 && c.opts.no_split_k) break;
         const double us = predict_instance(v, c.hw, d, split);
-        if (us > 0 && (!best || us < best_us)) { best = &d; best_us = us; best_split = split; }
+        // (equal prices: the lower instance id, whatever order the states were kept in)
+        if (us > 0 && (!best || us < best_us || (us == best_us && d.id < best->id))) { best = &d; best_us = us; best_split = split; }
       }
     }
     const double us0 = predict(v, c.hw, e.tile[0][0], e.tile[1][0], e.tile[2][0], e.tile[0][1], e.tile[1][1], e.tile[2][1],
@@ -487,6 +506,7 @@ gensor_status construct_internal(const gensor_problem* p, const gensor_hw* hw, c
   if (!best) return GENSOR_ERR_NO_SCHEDULE;
   schedule_from_instance(*best, out);
   out->split_k = best_split;
+  out->round_units = c.hw.compute_units;
   out->predicted_us = best_us;
   out->iterations = max_steps;
   out->chains = c.opts.chains;

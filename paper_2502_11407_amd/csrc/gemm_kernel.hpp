@@ -6,7 +6,9 @@
 //   BM,BN,BK   T_2  workgroup tile, staged in LDS                ("cache" primitive)
 //   WM,WN      T_1  wavefront tile, fp32 accumulators in registers
 //   MB         MFMA block edge (32: 32x32 blocks, 16: 16x16 blocks); fixes the MFMA k depth
-//   VM,VN      virtual-thread split: the wave tile is V strided pieces of T_0 = T_1/V rows
+//   VM,VN      virtual threads (setVThread, Eq. 3): the rows that one quarter wave reads together
+//              from the LDS tile of the m (A) or n (B) operand are interleaved over V bank phases;
+//              V = 1 is the plain layout, whose fragment reads conflict ceil(x / W) ways
 //   STAGES     LDS buffers (1: single buffer, 2: double buffer, 3 and more: a ring that keeps STAGES-1
 //              k tiles in flight; direct staging only)
 //   VEC        global accesses are 16-byte vectors (true) or single elements (false)
@@ -19,8 +21,12 @@
 //        (k, n) is gathered from the NCHW input, zero outside the image; m = filter.
 //
 // LDS layouts.  k-contiguous tiles are [rows][BK] in 16-byte chunks; chunk c of row r sits
-// at chunk c ^ ((r / rows_per_256B) % chunks_per_row), which makes a wave's b128 fragment
-// reads hit 64 distinct banks per 16 lanes.  n-contiguous tiles are [BK][BN + pad].
+// at chunk c ^ ((r / rows_per_256B) % V).  The 16 rows that a quarter wave's b128 fragment read
+// touches span x = 16 * min(row bytes, 256) bytes, i.e. ceil(x / (V * 256)) of them share each
+// bank: with V = chunks per row the read hits 64 distinct banks.  n-contiguous tiles are
+// [BK][BN + pad]; their V is the number of k rows that the pad (or, direct-staged, an XOR of the
+// column bytes) spreads over different banks: 4 rows are read together by a transposing 16-bit
+// read (pad 0 / 32 / 64 bytes for V = 1 / 2 / 4), 2 by a 32-bit one (pad 0 / 32).
 //
 // MFMA operand convention (per lane l of a 64-wide wave):
 //   32x32 blocks: row/col = l % 32, holds the 16-byte chunk  2*kstep + l/32  of that row
@@ -174,7 +180,12 @@ struct Cfg {
   // (direct staging deposits whole 1 KB runs, so there the rows are unpadded and 32-byte
   // column segments are XOR-swizzled with the k row instead)
   static constexpr bool NC_DIRECT = DIRECT_ && BSRC_ == B_NC;
-  static constexpr int PITCH_N = NC_DIRECT ? BN * ES : BN * ES + 32;
+  static constexpr int V_MAX_K = CPR;                        // deepest interleave of a k-contiguous tile
+  static constexpr int V_MAX_N = (ES == 2) ? 4 : 2;          // ... of an n-contiguous tile
+  // the pad puts consecutive k rows 64 bytes (V = 4) or 32 bytes (V = 2) apart modulo the 256 bytes of all banks
+  static constexpr int PAD_T = (VN >= 4) ? 64 : 32;
+  static constexpr int PAD_N = (VN == 1) ? 0 : (PAD_T + 2 * PAD_T - (BN * ES) % (2 * PAD_T)) % (2 * PAD_T);
+  static constexpr int PITCH_N = NC_DIRECT ? BN * ES : BN * ES + PAD_N;
   static constexpr int A_BYTES = BM * PITCH_K;
   static constexpr int B_BYTES = (BSRC == B_KC) ? BN * PITCH_K : BK * PITCH_N;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
@@ -184,7 +195,9 @@ struct Cfg {
   static constexpr int A_LOADS = (A_CHUNKS + THREADS - 1) / THREADS;
   static constexpr int B_LOADS = (B_CHUNKS + THREADS - 1) / THREADS;
   static_assert(BM % WM == 0 && BN % WN == 0, "wave tile must divide workgroup tile");
-  static_assert(WM % (MB * VM) == 0 && WN % (MB * VN) == 0, "virtual pieces must be whole MFMA blocks");
+  static_assert(WM % MB == 0 && WN % MB == 0, "wave tiles are whole MFMA blocks");
+  static_assert(VM >= 1 && (VM & (VM - 1)) == 0 && VM <= V_MAX_K, "V of the m operand: a power of two up to the chunks per row");
+  static_assert(VN >= 1 && (VN & (VN - 1)) == 0 && VN <= (BSRC == B_KC ? V_MAX_K : V_MAX_N), "V of the n operand");
   static_assert(BK % KG == 0, "BK must be a multiple of the fragment k extent");
   static_assert(MB == 32 || MB == 16, "MFMA block edge");
   static_assert(WAVES >= 1 && WAVES <= 16, "waves per workgroup");
@@ -198,11 +211,12 @@ struct Cfg {
   static_assert(STAGES <= 2 || (A_LOADS + B_LOADS) * (STAGES - 2) <= 63, "the load counter holds 63");
 };
 
-__device__ inline int swizzled_chunk(int row, int chunk, int rpp, int cpr) { return chunk ^ ((row / rpp) % cpr); }
-// Byte XOR applied inside an unpadded n-contiguous row of k row `krow`: the four rows a
-// 16-lane group of a transposing read touches land in four different 64-byte bank groups,
-// and rows 8 apart (the two groups of a 16x16-block read) in different 32-byte halves.
-__device__ inline int nc_swizzle(int krow) { return ((krow & 3) << 6) ^ (((krow >> 3) & 1) << 5); }
+__device__ inline int swizzled_chunk(int row, int chunk, int rpp, int v) { return chunk ^ ((row / rpp) % v); }
+// Byte XOR applied inside an unpadded n-contiguous row of k row `krow`: of the four rows a
+// 16-lane group of a transposing read touches, v land in different 64-byte bank groups (v = 4:
+// all of them), and with v = 4 rows 8 apart (the two groups of a 16x16-block read) in
+// different 32-byte halves.
+__device__ inline int nc_swizzle(int krow, int v) { return ((krow & (v - 1)) << 6) ^ (v >= 4 ? (((krow >> 3) & 1) << 5) : 0); }
 
 // ---------------------------------------------------------------- the kernel
 // SPLIT: the launch has split tiles (KernelArgs::split > 1); without it the kernel knows at compile time
@@ -322,7 +336,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 #pragma unroll
   for (int i = 0; i < C::A_LOADS; ++i) {
     const int q = tid + i * C::THREADS;
-    const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::CPR);
+    const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::VM);
     a_voff[i] = (uint32_t)((row * (int)args.lda + ch * EPC) * ES);
     a_kch[i] = ch * EPC;
   }
@@ -332,7 +346,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   for (int i = 0; i < C::B_LOADS; ++i) {
     const int q = tid + i * C::THREADS;
     if constexpr (C::BSRC == B_KC) {
-      const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::CPR);
+      const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::VN);
       b_voff[i] = (uint32_t)((row * (int)args.ldb + ch * EPC) * ES);
       b_kch[i] = ch * EPC;
     } else if constexpr (C::BSRC == B_NCS2) {
@@ -350,7 +364,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       constexpr int CPRN = BN * ES / 16;
       const int krow = q / CPRN;
       int ch = q % CPRN;
-      if constexpr (C::NC_DIRECT) ch ^= nc_swizzle(krow) >> 4;      // slot q receives the chunk the swizzle maps there
+      if constexpr (C::NC_DIRECT) ch ^= nc_swizzle(krow, C::VN) >> 4;      // slot q receives the chunk the swizzle maps there
       b_voff[i] = (uint32_t)((krow * (int)args.ldb + ch * EPC) * ES);
       b_kch[i] = krow;
     }
@@ -408,7 +422,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       for (int i = 0; i < C::A_LOADS; ++i) {
         const int q = tid + i * C::THREADS;
         if (C::A_CHUNKS % C::THREADS != 0 && q >= C::A_CHUNKS) break;
-        const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::CPR);
+        const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::VM);
         ra[i] = pack_chunk([&](int e) { return a_elem_bits(m0 + row, k0 + ch * EPC + e); });
       }
     } else {
@@ -435,7 +449,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         const int q = tid + i * C::THREADS;
         if (C::B_CHUNKS % C::THREADS != 0 && q >= C::B_CHUNKS) break;
         if constexpr (C::BSRC == B_KC) {
-          const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::CPR);
+          const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::VN);
           rb[i] = pack_chunk([&](int e) { return b_elem_bits(k0 + ch * EPC + e, n0 + row); });
         } else {
           constexpr int CPRN = BN * ES / 16;
@@ -510,14 +524,8 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   // are in flight while the MFMAs of step s issue.
   const int frow = lane % MB;          // row / column inside an MFMA block
   const int fgrp = lane / MB;          // which chunk of the k group this lane holds
-  auto block_row = [&](int bi) {       // first row of MFMA block bi of this wave inside the BM tile
-    constexpr int PER = C::MBLK / C::VM;
-    return (bi / PER) * (BM / C::VM) + wave_m * (C::WM / C::VM) + (bi % PER) * MB;
-  };
-  auto block_col = [&](int bj) {
-    constexpr int PER = C::NBLK / C::VN;
-    return (bj / PER) * (BN / C::VN) + wave_n * (C::WN / C::VN) + (bj % PER) * MB;
-  };
+  auto block_row = [&](int bi) { return wave_m * C::WM + bi * MB; };   // first row of MFMA block bi of this wave inside the BM tile
+  auto block_col = [&](int bj) { return wave_n * C::WN + bj * MB; };
   // One wave per SIMD (four waves of 128x128): nothing else covers a stall, so fragments are read
   // two k steps ahead (one register set per k step of a tile) and the barrier sits in front of step 2
   // (4096^3 on all-zero operands, where the power limit does not interfere: 88.0 -> 81.4 us; 8192^3 on
@@ -532,13 +540,13 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 #pragma unroll
     for (int bi = 0; bi < C::MBLK; ++bi) {
       const int row = block_row(bi) + frow;
-      fa[buf][bi] = *(GENSOR_LDS u32x4*)(abase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16);
+      fa[buf][bi] = *(GENSOR_LDS u32x4*)(abase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::VM) * 16);
     }
 #pragma unroll
     for (int bj = 0; bj < C::NBLK; ++bj) {
       if constexpr (C::BSRC == B_KC) {
         const int row = block_col(bj) + frow;
-        fb[buf][bj] = *(GENSOR_LDS u32x4*)(bbase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::CPR) * 16);
+        fb[buf][bj] = *(GENSOR_LDS u32x4*)(bbase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::VN) * 16);
       } else if constexpr (ES == 4) {
         // fp32, [k][n] tile: element t of this lane's chunk is k = ks*KG + fgrp*4 + t
         const int col = block_col(bj) + frow;
@@ -547,7 +555,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         for (int tt = 0; tt < 4; ++tt)
         {
           const int kr = ks * C::KG + fgrp * 4 + tt;
-          const int cb = C::NC_DIRECT ? ((col * 4) ^ nc_swizzle(kr)) : col * 4;
+          const int cb = C::NC_DIRECT ? ((col * 4) ^ nc_swizzle(kr, C::VN)) : col * 4;
           v[tt] = *(GENSOR_LDS uint32_t*)(bbase + kr * C::PITCH_N + cb);
         }
         fb[buf][bj] = v;
@@ -564,8 +572,8 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
           krow = ks * C::KG + g * 8 + (s >> 2);
           col = block_col(bj) + (s & 3) * 4;
         }
-        const int cb0 = C::NC_DIRECT ? ((col * 2) ^ nc_swizzle(krow)) : col * 2;
-        const int cb1 = C::NC_DIRECT ? ((col * 2) ^ nc_swizzle(krow + 4)) : col * 2;
+        const int cb0 = C::NC_DIRECT ? ((col * 2) ^ nc_swizzle(krow, C::VN)) : col * 2;
+        const int cb1 = C::NC_DIRECT ? ((col * 2) ^ nc_swizzle(krow + 4, C::VN)) : col * 2;
         GENSOR_LDS char* p = bbase + krow * C::PITCH_N;
         s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + cb0));
         s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + 4 * C::PITCH_N + cb1));

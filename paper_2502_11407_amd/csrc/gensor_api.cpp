@@ -185,10 +185,10 @@ static size_t pointwise_workspace(const GemmView& v) {
 // Split-k plan of instance d on view v with split factor `split`: the tiles that do not fill a whole
 // round of compute units (all of them when there are fewer tiles than units) are computed by `split`
 // workgroups each.  whole = tiles left unsplit; a plan with whole == tiles splits nothing.
-SplitPlan split_plan(const InstanceDesc& d, const GemmView& v, int split) {
+SplitPlan split_plan(const InstanceDesc& d, const GemmView& v, int split, int round_units) {
   SplitPlan pl;
   const int64_t tiles = ((v.M + d.bm - 1) / d.bm) * ((v.N + d.bn - 1) / d.bn) * v.batch;
-  const int64_t cus = gensor_hw_mi355x()->compute_units;
+  const int64_t cus = round_units > 0 ? round_units : gensor_hw_mi355x()->compute_units;
   pl.whole = split > 1 ? tiles / cus * cus : tiles;
   pl.split = pl.whole == tiles ? 1 : split;
   const int64_t waves = d.threads / 64;
@@ -219,7 +219,7 @@ extern "C" size_t gensor_workspace_bytes(const gensor_schedule* s, const gensor_
     // a split-k schedule: one counter per wave of every split tile, then one fp32 tile per part
     if (s->split_k <= 1 || gemm_view(p, &v) != GENSOR_OK) return 0;
     const InstanceDesc* d = find_instance(s, v);
-    return d && split_allowed(*d, v, s->split_k) ? split_plan(*d, v, s->split_k).bytes : 0;
+    return d && split_allowed(*d, v, s->split_k) ? split_plan(*d, v, s->split_k, s->round_units).bytes : 0;
   }
   if (!p || p->op != GENSOR_OP_CONV2D || gemm_view(p, &v) != GENSOR_OK || gemm_view(p, &w, VIEW_PREPASS) != GENSOR_OK) return 0;
   const size_t need_pw = pointwise_workspace(w);
@@ -234,7 +234,8 @@ extern "C" size_t gensor_workspace_bytes(const gensor_schedule* s, const gensor_
 // ------------------------------------------------------------------------------------
 namespace {
 std::mutex g_memo_mutex;
-std::map<std::tuple<int, int, int, int, int, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int>, gensor_schedule> g_memo;
+std::map<std::tuple<int, int, int, int, int, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t>, gensor_schedule> g_memo;
+const size_t kMemoLimit = 4096;      // shapes remembered; a full memo is emptied (a shape seen again is constructed again)
 
 gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, int view_mode, bool no_split, gensor_schedule* out) {
   auto key = std::make_tuple((int)p->op, (int)p->in_dtype, (int)p->out_dtype, (int)p->transB,
@@ -243,7 +244,7 @@ gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, int view_m
                              p->op == GENSOR_OP_CONV2D ? p->h : p->N, p->op == GENSOR_OP_CONV2D ? p->w : p->K,
                              p->op == GENSOR_OP_CONV2D ? p->k : 0, p->op == GENSOR_OP_CONV2D ? p->r : 0,
                              p->op == GENSOR_OP_CONV2D ? p->s : 0,
-                             p->op == GENSOR_OP_CONV2D ? (int)(p->stride * 64 + p->pad) : 0);
+                             p->op == GENSOR_OP_CONV2D ? p->stride : 0, p->op == GENSOR_OP_CONV2D ? p->pad : 0);
   std::lock_guard<std::mutex> lock(g_memo_mutex);
   auto it = g_memo.find(key);
   if (it != g_memo.end()) { *out = it->second; return GENSOR_OK; }
@@ -251,7 +252,10 @@ gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, int view_m
   std::memset(&opts, 0, sizeof(opts));
   opts.no_split_k = no_split ? 1 : 0;
   gensor_status st = construct_internal(p, nullptr, &opts, 0, vec_ok, view_mode, out);
-  if (st == GENSOR_OK) g_memo[key] = *out;
+  if (st == GENSOR_OK) {
+    if (g_memo.size() >= kMemoLimit) g_memo.clear();
+    g_memo[key] = *out;
+  }
   return st;
 }
 
@@ -270,7 +274,7 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
     s = &local;
   }
   const InstanceDesc* d = find_instance(s, v);
-  if (constructed && d && s->split_k > 1 && workspace_bytes < split_plan(*d, v, s->split_k).bytes) {
+  if (constructed && d && s->split_k > 1 && workspace_bytes < split_plan(*d, v, s->split_k, s->round_units).bytes) {
     // the workspace is too small for the split the ranking chose: the best unsplit schedule instead
     gensor_status st = memoised_schedule(p, vec_ok, mode, true, &local);
     if (st != GENSOR_OK) return st;
@@ -280,11 +284,13 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
   if (d->vec && !vec_ok) return GENSOR_ERR_NO_SCHEDULE;          // schedule asks for vector accesses the operands cannot give
   if (d->direct && !d->units && v.K % d->bk != 0) return GENSOR_ERR_NO_SCHEDULE;
   if (s->split_k < 1 || !split_allowed(*d, v, s->split_k)) return GENSOR_ERR_NO_SCHEDULE;
-  SplitPlan sp = split_plan(*d, v, s->split_k);
+  SplitPlan sp = split_plan(*d, v, s->split_k, s->round_units);
   if (sp.split > 1 && (!ws_aligned || workspace_bytes < sp.bytes)) return GENSOR_ERR_WORKSPACE;
   // 32-bit offsets inside one workgroup tile
   const int64_t lim = 0x7fffffffll;
-  if ((int64_t)(d->bm + 1) * lda * v.esize >= lim || (int64_t)(d->bm + 1) * ldc * v.osize >= lim) return GENSOR_ERR_UNSUPPORTED;
+  if ((int64_t)(d->bm + 1) * lda * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
+  // (the convolution epilogues address the output with 64-bit indices and never use ldc)
+  if (v.bsrc != B_CONV && (int64_t)(d->bm + 1) * ldc * v.osize >= lim) return GENSOR_ERR_UNSUPPORTED;
   if (v.bsrc == B_KC && (int64_t)(d->bn + 1) * ldb * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
   if ((v.bsrc == B_NC || v.bsrc == B_NCS2) && ((int64_t)(d->bk + 1) * ldb + d->bn) * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
 

@@ -45,7 +45,8 @@ struct SplitPlan {
   int64_t counter_bytes;   // arrival counters at the start of the workspace, padded to 256 bytes
   size_t bytes;            // counters + partial tiles
 };
-SplitPlan split_plan(const InstanceDesc& d, const GemmView& v, int split);
+// round_units: the compute units a round of tiles is dealt over (gensor_schedule::round_units; 0: the MI355X's).
+SplitPlan split_plan(const InstanceDesc& d, const GemmView& v, int split, int round_units);
 bool split_allowed(const InstanceDesc& d, const GemmView& v, int split);
 
 // gensor_construct with two more inputs: whether the operands allow 16-byte vector accesses

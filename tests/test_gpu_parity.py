@@ -391,13 +391,14 @@ def test_mfma_probe_counts_its_flops(gs, dtype):
     """The measurement aid really executes iters x 8 MFMAs per wavefront: with all-ones operands every
     accumulator element ends at 16 * iters, so a lane's sum over its 8 x 16 values is 2048 * iters."""
     import torch
+    from paper_2502_11407_amd import probe
     ones = inputs.to_storage(np.ones(128 * 1024, dtype=np.float32), dtype)
     sink = torch.zeros(256 * 256, dtype=torch.float32, device="cuda")
-    gs.mfma_probe(dtype, gs.to_device(ones, dtype), sink, 10)
+    probe.mfma_probe(dtype, gs.to_device(ones, dtype), sink, 10, 256)
     torch.cuda.synchronize()
     assert torch.all(sink == 2048.0 * 10).item()
     with pytest.raises(gs.GensorError):
-        gs.mfma_probe("f32", gs.to_device(np.ones(64 * 1024, dtype=np.float32), "f32"), sink, 10)
+        probe.mfma_probe("f32", gs.to_device(np.ones(64 * 1024, dtype=np.float32), "f32"), sink, 10, 256)
 
 
 # ------------------------------------------------------------------ GEMV and AvgPooling2d
