@@ -189,6 +189,24 @@ gensor_status gensor_gemm(const gensor_schedule* s, const gensor_problem* p, flo
                           float beta, void* C, int64_t ldc,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * gensor_gemm for callers that cannot allocate device memory for a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same operator, the same
+ * kernels and the same results, with the split-k counters and partial tiles kept in a device array
+ * of GENSOR_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the library
+ * runs on holds its own copy until the process ends).  The call allocates and frees nothing.
+ * A schedule whose gensor_workspace_bytes(s, p) exceeds GENSOR_STATIC_SCRATCH_BYTES is refused with
+ * GENSOR_ERR_WORKSPACE and nothing is launched; with s == NULL split-k schedules are ranked and one
+ * that does not fit falls back to the best unsplit schedule, as in gensor_gemm.  Every call on one
+ * GPU shares that GPU's array, which keeps the last call's contents (the call clears the counters it
+ * uses itself): calls that overlap in time on one GPU -- different streams, or graphs replayed
+ * concurrently -- race on it and must be serialised by the caller.
+ */
+#define GENSOR_STATIC_SCRATCH_BYTES (32 * 1024 * 1024 + 65536)
+gensor_status gensor_gemm_static_scratch(const gensor_schedule* s, const gensor_problem* p, float alpha,
+                                         const void* A, int64_t lda, const void* B, int64_t ldb,
+                                         float beta, void* C, int64_t ldc, void* hip_stream);
+
 /* The same for every b < p->batch; consecutive matrices are stride{A,B,C} elements
  * apart (a stride of 0 broadcasts that operand). */
 gensor_status gensor_bmm(const gensor_schedule* s, const gensor_problem* p, float alpha,

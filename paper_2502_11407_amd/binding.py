@@ -23,7 +23,7 @@ OP_GEMM, OP_BMM, OP_CONV2D = 0, 1, 2
 
 EXPORTS = ["gensor_hw_mi355x", "gensor_construct", "gensor_construct_trace", "gensor_predict_us",
            "gensor_num_instances", "gensor_instance_schedule", "gensor_gemm", "gensor_bmm", "gensor_conv2d",
-           "gensor_workspace_bytes", "gensor_status_string", "gensor_gemv", "gensor_avgpool2d"]
+           "gensor_workspace_bytes", "gensor_status_string", "gensor_gemm_static_scratch", "gensor_gemv", "gensor_avgpool2d"]
 
 
 class Problem(C.Structure):
@@ -96,6 +96,8 @@ def _load():
     L.gensor_predict_us.argtypes = [S, P, C.POINTER(Hw)]
     L.gensor_gemm.restype = i32
     L.gensor_gemm.argtypes = [S, P, f32, vp, i64, vp, i64, f32, vp, i64, vp, C.c_size_t, vp]
+    L.gensor_gemm_static_scratch.restype = i32
+    L.gensor_gemm_static_scratch.argtypes = [S, P, f32, vp, i64, vp, i64, f32, vp, i64, vp]
     L.gensor_bmm.restype = i32
     L.gensor_bmm.argtypes = [S, P, f32, vp, i64, i64, vp, i64, i64, f32, vp, i64, i64, vp, C.c_size_t, vp]
     L.gensor_conv2d.restype = i32
@@ -210,6 +212,17 @@ def gemm(p: Problem, A, B, Cout, alpha: float = 1.0, beta: float = 0.0, schedule
                          B.data_ptr(), ldb if ldb is not None else B.stride(0), beta,
                          Cout.data_ptr(), ldc if ldc is not None else Cout.stride(0), ws_ptr, ws_len, _stream_ptr(stream))
     _check(st, "gensor_gemm")
+
+
+STATIC_SCRATCH_BYTES = 32 * 1024 * 1024 + 65536
+
+
+def gemm_static_scratch(p: Problem, A, B, Cout, alpha: float = 1.0, beta: float = 0.0, schedule: Optional[Schedule] = None,
+                        stream=None):
+    """gemm() with the split-k workspace taken from the library's own device array (nothing is allocated)."""
+    st = lib.gensor_gemm_static_scratch(_sref(schedule), C.byref(p), alpha, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0),
+                                        beta, Cout.data_ptr(), Cout.stride(0), _stream_ptr(stream))
+    _check(st, "gensor_gemm_static_scratch")
 
 
 def bmm(p: Problem, A, B, Cout, alpha: float = 1.0, beta: float = 0.0, schedule: Optional[Schedule] = None,

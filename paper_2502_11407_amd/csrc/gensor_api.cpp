@@ -358,6 +358,45 @@ extern "C" gensor_status gensor_gemm(const gensor_schedule* s, const gensor_prob
   return gensor_bmm(s, p, alpha, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, workspace, workspace_bytes, hip_stream);
 }
 
+// ------------------------------------------------------------------------------------
+// gensor_gemm for callers that cannot bring a workspace: the split-k counters and partial tiles
+// live in a device array that is part of this library's code object.
+// ------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[GENSOR_STATIC_SCRATCH_BYTES];
+
+namespace {
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[64];          // per device ordinal: where that device's copy of `scratch` lives
+
+// The address of this device's copy of the array (each device holds its own, at its own address);
+// looked up once per device, with that device current.
+gensor_status static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GENSOR_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return GENSOR_ERR_DEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return GENSOR_OK;
+}
+}  // namespace
+
+extern "C" gensor_status gensor_gemm_static_scratch(const gensor_schedule* s, const gensor_problem* p, float alpha,
+                                                    const void* A, int64_t lda, const void* B, int64_t ldb,
+                                                    float beta, void* C, int64_t ldc, void* hip_stream) {
+  if (!p || p->op != GENSOR_OP_GEMM) return GENSOR_ERR_INVALID_ARG;
+  if (s && gensor_workspace_bytes(s, p) > (size_t)GENSOR_STATIC_SCRATCH_BYTES) return GENSOR_ERR_WORKSPACE;
+  void* ptr = nullptr;
+  gensor_status st = static_scratch(&ptr);
+  if (st != GENSOR_OK) return st;
+  // from here on the array is a workspace like any other: the counters at its start are cleared by the
+  // fill kernel in front of the operator, the partial tiles are written before they are read
+  return gensor_bmm(s, p, alpha, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, ptr, (size_t)GENSOR_STATIC_SCRATCH_BYTES, hip_stream);
+}
+
 extern "C" gensor_status gensor_conv2d(const gensor_schedule* s, const gensor_problem* p,
                                        const void* input, const void* weight, void* output,
                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
