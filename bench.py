@@ -1,19 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the scheduled dense operators on one MI355X.
 
-One JSON line on stdout.  A "step" is one launch of the headline operator: the fp16 GEMM
-M=N=K=4096 (fp32 accumulate and output, A row-major, B column-major) with the schedule
-gensor_construct picked for it; inputs are resident in HBM before the timed region.
-`value` is its TFLOP/s.  The same line carries
-  roofline      dense fp16 MFMA peak against the measured kernel time (HIP events on the
-                stream the kernel runs on)
+ONE short JSON line on stdout (under 4 KB).  A "step" is one launch of the headline operator: the
+fp16 GEMM M=N=K=4096 (fp32 accumulate and output, A row-major, B column-major) with the schedule
+gensor_construct picked for it; inputs are resident in HBM before the timed region.  `value` is its
+TFLOP/s over exactly --steps launches.  The same line carries
+  roofline      dense fp16 MFMA peak against the measured kernel time (HIP events on the stream the
+                kernel runs on)
   cpu_baseline  the CPU oracle timed on a bounded slice of the same GEMM
-  operators     every other benchmark shape (fp32 GEMM, GPT-2 GEMMs, attention-score
-                BMM, ResNet-50 convolutions) timed the same way (median of 5 batches), with
-                the fraction of its own roofline ceiling min(MFMA peak, flop/byte x HBM
-                peak), a cold-cache time (operand sets rotated through more than the 256 MB
-                Infinity Cache), schedule-construction wall time and a sampled parity error
-                against the oracle
+  operators     one compact row per benchmark configuration (fp32 GEMM, the headline, GPT-2 GEMMs,
+                attention-score BMM, ResNet-50 convolutions): us, tf (TFLOP/s), pk (% of the dense MFMA
+                peak of its type), ceil (% of its own roofline ceiling min(MFMA peak, flop/byte x HBM
+                peak)), gbs (GB/s on algorithmic bytes), id (kernel instance), cs (construction
+                seconds), err (sampled relative Frobenius error against the oracle)
+Every row but the headline's `value` is timed by one protocol that does not depend on --steps: launches
+that settle the shader clock, then the median of 5 event-bracketed batches of at least 50 launches.
+The long sections (per-shape details, unbalanced and deep-k GEMMs, output-type variants, the other
+operators of the paper's table, the walk ablation) go to the file named by --details
+(default gpurun_out/bench_details.json); one progress line per section goes to stderr.
 """
 import argparse
 import json
@@ -28,9 +32,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "f32": 157.3}   # dense MFMA, MI355X
 HBM_GBS = 8000.0
-# HBM bytes per launch of the headline kernel from the FETCH_SIZE / WRITE_SIZE counter passes (each scaled by
-# the same counter's reading for a 256 MiB device copy); keyed by (tile, wave tile, direct) of the instance
-# they were measured on.  Any other instance reports null.
+# HBM-side bytes per launch of the headline kernel.  Not measured in this run (hardware counters need the
+# profiler): the figures of the FETCH_SIZE / WRITE_SIZE counter passes recorded in TRAFFIC_SOURCE, each scaled by
+# the same counter's reading for a 256 MiB device copy; keyed by (tile, wave tile, direct) of the instance they
+# were measured on.  Any other instance reports null.
+TRAFFIC_SOURCE = "profiles/gemm_f16_4096_kernel_trace.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes, copy-calibrated)"
 MEASURED_TRAFFIC_BYTES = {((256, 256, 64), (128, 128), 1): 268.9e6, ((256, 256, 64), (128, 64), 1): 269.4e6,
                           ((256, 256, 64), (64, 128), 1): 269.4e6}
 
@@ -103,12 +109,22 @@ class Case:
         del self.sets[1:]
         return e0.elapsed_time(e1) / launches, n_sets
 
-    def time_median_ms(self, steps, warmup, batches=5):
-        """Median over `batches` event-bracketed batches of `steps` launches."""
+    def time_median_ms(self, batches=5, min_launches=50, settle_ms=25.0, batch_ms=4.0):
+        """The protocol of every row: launches that keep the chip busy for settle_ms (the shader clock
+        needs tens of milliseconds of load to settle after an idle period), then the median over
+        `batches` event-bracketed batches of at least `min_launches` launches (more for short kernels:
+        a batch lasts about batch_ms)."""
         import torch
-        for _ in range(warmup):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
             self.launch()
+        e1.record()
         torch.cuda.synchronize()
+        per = max(1e-3, e0.elapsed_time(e1) / 10)
+        for _ in range(int(min(3000, max(20, settle_ms / per)))):
+            self.launch()
+        steps = int(min(2000, max(min_launches, batch_ms / per)))
         out = []
         for _ in range(batches):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -118,6 +134,7 @@ class Case:
             e1.record()
             torch.cuda.synchronize()
             out.append(e0.elapsed_time(e1) / steps)
+        self.protocol = {"batches": batches, "launches_per_batch": steps, "spread_pct": 100.0 * (max(out) - min(out)) / min(out)}
         return sorted(out)[len(out) // 2]
 
     def time_ms(self, steps, warmup):
@@ -204,24 +221,14 @@ def _graph_us(fn, launches=20, replays=10, warm_replays=3):
     return e0.elapsed_time(e1) * 1e3 / (launches * replays)
 
 
-def _median_ms(fn, steps, warmup=5, batches=5):
-    import torch
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
-    out = []
-    for _ in range(batches):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        out.append(e0.elapsed_time(e1) / steps)
-    return sorted(out)[len(out) // 2]
+def _median_ms(fn, batches=5, min_launches=50, settle_ms=25.0, batch_ms=4.0):
+    """Case.time_median_ms for a plain callable."""
+    c = Case.__new__(Case)
+    c.launch = lambda which=0: fn()
+    return Case.time_median_ms(c, batches, min_launches, settle_ms, batch_ms)
 
 
-def variant_rows(gs, inputs, steps):
+def variant_rows(gs, inputs):
     """The benchmark shapes in their other stated forms: the 16-bit-input shapes with output in the input type
     (half the store traffic, so another roofline), and the attention scores with K^T laid out in memory."""
     import torch
@@ -231,7 +238,7 @@ def variant_rows(gs, inputs, steps):
     rows = []
     for wl, out_dtype in todo:
         c = Case(gs, inputs, wl, out_dtype=out_dtype)
-        m = c.time_median_ms(steps, 20)
+        m = c.time_median_ms()
         nbytes = _algorithmic_bytes(wl, inputs, out_dtype)
         tf = wl.flops / (m * 1e-3) / 1e12
         ceiling = min(PEAK_TFLOPS[wl.dtype], wl.flops / nbytes * HBM_GBS / 1e3)
@@ -255,9 +262,9 @@ def deep_k_rows(gs, inputs):
     for i in range(len(inputs.DEEP_K_GEMMS)):
         wl = inputs.deep_k_gemm(i)
         c = Case(gs, inputs, wl)
-        m = c.time_median_ms(30, 5)
+        m = c.time_median_ms()
         c1 = Case(gs, inputs, wl, opts=gs.ConstructOpts(0, 0, 0, 0, 0, 0, 1, 0))
-        m1 = c1.time_median_ms(10, 3)
+        m1 = c1.time_median_ms(batches=3, min_launches=20)
         rows.append({"workload": wl.name, "us": m * 1e3, "tflops": wl.flops / (m * 1e-3) / 1e12,
                      "kernel_id": c.sched.kernel_id, "split_k": c.sched.split_k, "predicted_us": c.sched.predicted_us,
                      "workspace_MB": gs.workspace_bytes(c.p, c.sched) / 1e6,
@@ -277,7 +284,7 @@ def operator_table_rows(gs, inputs):
     for i in range(len(inputs.PAPER_CONVS)):
         wl = inputs.paper_conv(i)
         c = Case(gs, inputs, wl)
-        m = c.time_median_ms(30, 5)
+        m = c.time_median_ms()
         nbytes = _algorithmic_bytes(wl, inputs)
         tf = wl.flops / (m * 1e-3) / 1e12
         ceiling = min(PEAK_TFLOPS[wl.dtype], wl.flops / nbytes * HBM_GBS / 1e3)
@@ -290,7 +297,7 @@ def operator_table_rows(gs, inputs):
         A, x = inputs.gemv_workload(i)
         dA, dx = gs.to_device(A, "f16"), gs.to_device(x, "f16")
         y = torch.empty(M, dtype=torch.float32, device="cuda")
-        m = _median_ms(lambda: gs.gemv("f16", dA, dx, y), 30)
+        m = _median_ms(lambda: gs.gemv("f16", dA, dx, y))
         in_graph = _graph_us(lambda: gs.gemv("f16", dA, dx, y))
         nbytes = 2 * (M * N + N) + 4 * M
         sel = inputs.sample_indices(7, (M,), 64)[:, 0]
@@ -306,7 +313,7 @@ def operator_table_rows(gs, inputs):
         shape = ops.pool_out_shape(*I.shape, f, stride)
         dI = gs.to_device(I, "f16")
         O = gs.empty_device(shape)
-        m = _median_ms(lambda: gs.avgpool2d("f16", dI, O, f, stride), 30)
+        m = _median_ms(lambda: gs.avgpool2d("f16", dI, O, f, stride))
         in_graph = _graph_us(lambda: gs.avgpool2d("f16", dI, O, f, stride))
         nbytes = 2 * I.size + 4 * int(np.prod(shape))
         co = inputs.sample_indices(7, shape, 256)
@@ -343,8 +350,8 @@ def ablation(gs, inputs):
             except gs.GensorError as e:
                 row[vname] = {"error": str(e)}
                 continue
-            m = c.time_median_ms(30, 100, batches=3)
-            row[vname] = {"kernel_id": c.sched.kernel_id, "us": m * 1e3, "tflops": wl.flops / (m * 1e-3) / 1e12,
+            m = c.time_median_ms(batches=3)
+            row[vname] = {"kernel_id": c.sched.kernel_id, "vthread": [c.sched.vthread[0], c.sched.vthread[1]], "us": m * 1e3, "tflops": wl.flops / (m * 1e-3) / 1e12,
                           "predicted_us": c.sched.predicted_us, "states_scored": c.sched.states_scored,
                           "construct_s": c.construct_s}
             del c
@@ -371,6 +378,31 @@ def cpu_baseline(w):
             "sample": f"first {rows2} of {w.M} rows of C (all {w.N} columns, full K={w.K}), {dt:.1f} s"}
 
 
+def _row(c, wl, m, inputs, out_dtype="f32"):
+    nbytes = _algorithmic_bytes(wl, inputs, out_dtype)
+    tf = wl.flops / (m * 1e-3) / 1e12
+    ceiling = min(PEAK_TFLOPS[wl.dtype], wl.flops / nbytes * HBM_GBS / 1e3)
+    return {"workload": wl.name, "dtype": wl.dtype, "us": m * 1e3, "tflops": tf,
+            "pct_of_mfma_peak": 100.0 * tf / PEAK_TFLOPS[wl.dtype], "algorithmic_GBs": nbytes / (m * 1e-3) / 1e9,
+            "pct_of_hbm_peak": 100.0 * nbytes / (m * 1e-3) / 1e9 / HBM_GBS, "roofline_ceiling_tflops": ceiling,
+            "pct_of_roofline_ceiling": 100.0 * tf / ceiling, "construct_s": c.construct_s, "kernel_id": c.sched.kernel_id,
+            "schedule": "%dx%dx%d wave %dx%d V %d,%d stages %d direct %d split %d" % (
+                c.sched.tile[0][0], c.sched.tile[1][0], c.sched.tile[2][0], c.sched.tile[0][1], c.sched.tile[1][1],
+                c.sched.vthread[0], c.sched.vthread[1], c.sched.stages, c.sched.direct_lds, c.sched.split_k),
+            "protocol": c.protocol}
+
+
+def _compact(name, r):
+    g = lambda x, n: None if x is None else float(("%." + str(n) + "g") % x)
+    return {"w": name, "us": g(r["us"], 4), "tf": g(r["tflops"], 4), "pk": g(r["pct_of_mfma_peak"], 3),
+            "ceil": g(r["pct_of_roofline_ceiling"], 3), "gbs": g(r["algorithmic_GBs"], 4), "id": r["kernel_id"],
+            "cs": g(r["construct_s"], 2), "err": g(r.get("parity_rel_frobenius_sampled"), 2)}
+
+
+def _progress(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -382,9 +414,14 @@ def main():
                     help="skip the launches that settle the shader clock ahead of the warm-up (hardware-counter passes)")
     ap.add_argument("--launch-only", default="",
                     help="comma-separated workload names (cfg1..cfg5_1x1s2, u0..u4, d0..d3): construct, launch each "
-                         "20 times and exit -- what a hardware-counter pass over one of the other shapes runs")
+                         "20 times and exit -- what a hardware-counter pass over one of the other shapes runs; "
+                         "name:no_vthread constructs without setVThread")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy, the known-size reference for HBM byte counters")
+    ap.add_argument("--details", default=os.path.join(ROOT, "gpurun_out", "bench_details.json"),
+                    help="file that receives the long sections (the stdout line stays short)")
+    ap.add_argument("--sections", default="operators,unbalanced,deep_k,variants,operator_table,ablation,cpu",
+                    help="comma-separated sections to run besides the headline")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (single-GPU operators, "
@@ -405,18 +442,20 @@ def main():
         del src, dst
 
     if args.launch_only:
-        for name in args.launch_only.split(","):
+        for item in args.launch_only.split(","):
+            name, _, variant = item.partition(":")
             wl = (inputs.unbalanced_gemm(int(name[1:])) if name[0] == "u" else
                   inputs.deep_k_gemm(int(name[1:])) if name[0] == "d" else inputs.all_configs()[name])
-            c = Case(gs, inputs, wl)
+            c = Case(gs, inputs, wl, gs.ConstructOpts(0, 0, 0, 0, 0, 1) if variant == "no_vthread" else None)
             for _ in range(20):
                 c.launch()
             torch.cuda.synchronize()
-            print(name, "kernel", c.sched.kernel_id, "split_k", c.sched.split_k)
+            print(item, "kernel", c.sched.kernel_id, "vthread", c.sched.vthread[0], c.sched.vthread[1], "split_k", c.sched.split_k)
             del c
             torch.cuda.empty_cache()
         return
 
+    sections = set() if args.only_headline else set(x for x in args.sections.split(",") if x)
     w = inputs.config2_gemm_f16()
     head = Case(gs, inputs, w)
     # the shader clock needs tens of milliseconds of load to settle after an idle period (the first ~100 launches run
@@ -430,7 +469,7 @@ def main():
     sd = head.sched.describe()
     traffic = MEASURED_TRAFFIC_BYTES.get(((sd["tile_m"][0], sd["tile_n"][0], sd["tile_k"][0]),
                                           (sd["tile_m"][1], sd["tile_n"][1]), sd["direct_lds"]))
-    cold_ms, cold_sets = (None, 0) if args.only_headline else head.time_cold_ms()
+    _progress("headline %.1f us over %d launches (kernel %d)" % (ms * 1e3, args.steps, head.sched.kernel_id))
     line = {
         "metric": "TFLOP/s and % of MFMA peak per operator on 1 MI355X; construction time (s)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -438,84 +477,99 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": "GEMM fp16 in / fp32 accumulate+out, M=N=K=4096, A row-major, B column-major, "
                                "uniform[-1,1) (configs[1])",
-                   "schedule": head.sched.describe()},
+                   "kernel_id": head.sched.kernel_id,
+                   "schedule": "%dx%dx%d wave %dx%d V %d,%d stages %d direct %d" % (
+                       sd["tile_m"][0], sd["tile_n"][0], sd["tile_k"][0], sd["tile_m"][1], sd["tile_n"][1],
+                       sd["vthread"][0], sd["vthread"][1], sd["stages"], sd["direct_lds"])},
         "pct_of_mfma_peak": 100.0 * tflops / peak,
         "construct_s": head.construct_s,
-        "wall_ms_per_step": wall_ms,
         "clock_settle_launches_before_warmup": settle,
-        "cold_cache": None if cold_ms is None else {"ms_per_step": cold_ms, "tflops": w.flops / (cold_ms * 1e-3) / 1e12,
-                                                    "operand_sets": cold_sets},
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": peak, "unit": "TFLOP/s",
-                     "frac": tflops / peak, "traffic": traffic},
+                     "frac": tflops / peak, "traffic": traffic,
+                     "traffic_source": TRAFFIC_SOURCE if traffic is not None else None},
     }
+    details = {"headline_schedule": sd, "wall_ms_per_step": wall_ms}
     prop = torch.cuda.get_device_properties(0)
     ghz = prop.clock_rate / 1e6 if hasattr(prop, "clock_rate") else 2.4
-    line["device"] = {
+    details["device"] = {
         "name": prop.name, "compute_units": prop.multi_processor_count, "clock_ghz": ghz,
         # one 32x32x16 16-bit MFMA (32768 flop) per SIMD every 32 cycles, one 32x32x2 fp32 MFMA (4096 flop) every 64
         "derived_peak_tflops": {"f16_bf16_mfma": prop.multi_processor_count * 4 * 1024 * ghz / 1e3,
                                 "f32_mfma": prop.multi_processor_count * 4 * 64 * ghz / 1e3},
         "published_peaks_used": {"f16_bf16_mfma_tflops": PEAK_TFLOPS["f16"], "f32_mfma_tflops": PEAK_TFLOPS["f32"], "hbm_GBs": HBM_GBS},
         "flop_convention": "GEMM 2MNK, BMM 2BMNK, conv 2 N K P Q C R S (padded taps counted)"}
-    if not args.only_headline:
-        # one launch at a time (graph replay, no overlap between the tail of one launch and the head of the next)
-        # (as many warm-up launches as the eager timing: the shader clock has to settle again after the idle gaps above)
-        line["us_in_graph"] = _graph_us(head.launch, launches=20, replays=25, warm_replays=15)
+    if "operators" in sections:
+        # the headline by the protocol of the other rows, and one launch at a time (graph replay: no overlap between the
+        # tail of one launch and the head of the next)
+        m = head.time_median_ms()
+        hrow = _row(head, w, m, inputs)
+        hrow["parity_rel_frobenius_sampled"] = head.parity()
+        cold_ms, cold_sets = head.time_cold_ms()
+        hrow["cold_us"] = cold_ms * 1e3
+        hrow["us_in_graph"] = _graph_us(head.launch, launches=20, replays=25, warm_replays=15)
         ceil_tf = mfma_ceiling(gs, inputs, w.dtype)
-        line["mfma_only_kernel_same_operand_distribution"] = {
-            "tflops": ceil_tf, "frac_of_it": tflops / ceil_tf,
-            "note": "a kernel of nothing but fp16 MFMAs on uniform[-1,1) operands, timed in this run: the chip's power "
-                    "limit holds it below the published peak, so this is the ceiling that applies to this workload"}
-        line["parity_rel_frobenius_sampled"] = head.parity()
-        ops_out = []
-        steps2 = min(200, max(10, args.steps // 4))
+        details["mfma_only_kernel_same_operand_distribution"] = {
+            "tflops": ceil_tf, "headline_frac_of_it": hrow["tflops"] / ceil_tf,
+            "note": "a kernel of nothing but fp16 MFMAs on uniform[-1,1) operands, timed in this run: what the chip's power "
+                    "limit allows for such values (context; the roofline above is against the published peak)"}
+        rows, compact = [], []
         for name, wl in inputs.all_configs().items():
             if name == "cfg2":
-                continue
-            c = Case(gs, inputs, wl)
-            m = c.time_median_ms(steps2, max(5, args.warmup // 4))
-            cold, _ = c.time_cold_ms()
-            in_graph = _graph_us(c.launch)
-            tf = wl.flops / (m * 1e-3) / 1e12
-            nbytes = _algorithmic_bytes(wl, inputs)
-            gb = nbytes / (m * 1e-3) / 1e9
-            ceiling = min(PEAK_TFLOPS[wl.dtype], wl.flops / nbytes * HBM_GBS / 1e3)     # TFLOP/s
-            ops_out.append({"workload": wl.name, "dtype": wl.dtype, "us": m * 1e3, "cold_us": cold * 1e3,
-                            "us_in_graph": in_graph, "tflops": tf,
-                            "pct_of_mfma_peak": 100.0 * tf / PEAK_TFLOPS[wl.dtype],
-                            "algorithmic_GBs": gb, "pct_of_hbm_peak": 100.0 * gb / HBM_GBS,
-                            "roofline_ceiling_tflops": ceiling, "pct_of_roofline_ceiling": 100.0 * tf / ceiling,
-                            "construct_s": c.construct_s, "kernel_id": c.sched.kernel_id,
-                            "schedule": "%dx%dx%d wave %dx%d stages %d direct %d" % (
-                                c.sched.tile[0][0], c.sched.tile[1][0], c.sched.tile[2][0], c.sched.tile[0][1],
-                                c.sched.tile[1][1], c.sched.stages, c.sched.direct_lds),
-                            "parity_rel_frobenius_sampled": c.parity(256)})
-            del c
-            torch.cuda.empty_cache()
-        line["operators"] = ops_out
+                r = hrow
+            else:
+                c = Case(gs, inputs, wl)
+                m = c.time_median_ms()
+                r = _row(c, wl, m, inputs)
+                cold, _ = c.time_cold_ms()
+                r["cold_us"] = cold * 1e3
+                r["us_in_graph"] = _graph_us(c.launch)
+                r["parity_rel_frobenius_sampled"] = c.parity(256)
+                del c
+                torch.cuda.empty_cache()
+            rows.append(r)
+            compact.append(_compact(name, r))
+            _progress("%s %.1f us, %.1f %% of its ceiling, kernel %d" % (name, r["us"], r["pct_of_roofline_ceiling"], r["kernel_id"]))
+        details["operators"] = rows
+        line["operators"] = compact
+        line["protocol"] = "rows: clock settle, then median of 5 batches of >=50 launches; value: the --steps launches"
+    if "unbalanced" in sections:
         # the paper's GEMM shapes with unbalanced dimensions (next in line after the five configurations)
         nxt = []
         for i in range(len(inputs.UNBALANCED_GEMMS)):
             wl = inputs.unbalanced_gemm(i)
             c = Case(gs, inputs, wl)
-            m = c.time_median_ms(max(5, min(steps2, int(20.0 / max(0.02, wl.flops / 1.0e12)))), 5)
-            tf = wl.flops / (m * 1e-3) / 1e12
-            nbytes = _algorithmic_bytes(wl, inputs)
-            ceiling = min(PEAK_TFLOPS[wl.dtype], wl.flops / nbytes * HBM_GBS / 1e3)
-            nxt.append({"workload": wl.name, "us": m * 1e3, "tflops": tf, "algorithmic_GBs": nbytes / (m * 1e-3) / 1e9,
-                        "roofline_ceiling_tflops": ceiling, "pct_of_roofline_ceiling": 100.0 * tf / ceiling,
-                        "kernel_id": c.sched.kernel_id, "construct_s": c.construct_s,
-                        "parity_rel_frobenius_sampled": c.parity(128)})
+            m = c.time_median_ms(min_launches=50 if wl.flops < 2e11 else 10)
+            r = _row(c, wl, m, inputs)
+            r["parity_rel_frobenius_sampled"] = c.parity(128)
+            nxt.append(r)
+            _progress("%s %.1f us kernel %d" % (wl.name, r["us"], r["kernel_id"]))
             del c, wl
             torch.cuda.empty_cache()
-        line["unbalanced_gemms"] = nxt
-        line["deep_k_gemms"] = deep_k_rows(gs, inputs)
-        line["variants"] = variant_rows(gs, inputs, steps2)
-        line["operator_table"] = operator_table_rows(gs, inputs)
-        line["ablation"] = ablation(gs, inputs)
+        details["unbalanced_gemms"] = nxt
+    if "deep_k" in sections:
+        details["deep_k_gemms"] = deep_k_rows(gs, inputs)
+        _progress("deep-k rows done")
+    if "variants" in sections:
+        details["variants"] = variant_rows(gs, inputs)
+        _progress("output-type variants done")
+    if "operator_table" in sections:
+        details["operator_table"] = operator_table_rows(gs, inputs)
+        _progress("operator table done")
+    if "ablation" in sections:
+        details["ablation"] = ablation(gs, inputs)
+        line["ablation"] = [{"w": row["workload"], **{k: [v.get("kernel_id"), None if "us" not in v else float("%.4g" % v["us"])]
+                                                     for k, v in row.items() if isinstance(v, dict)}} for row in details["ablation"]]
+        _progress("ablation done")
+    if "cpu" in sections:
         line["cpu_baseline"] = cpu_baseline(w)
-        line["paper_context"] = ("paper (RTX 4090, precision not stated): GEMM 45.2 TFLOP/s, Conv2d C1 34.54 TFLOP/s, "
-                                 "construction 'a few seconds' (Table VI, Fig. 8 caption)")
+    line["paper_context"] = "paper (RTX 4090, precision not stated): GEMM 45.2 TFLOP/s, Conv2d C1 34.54 TFLOP/s, construction 'a few seconds'"
+    try:
+        os.makedirs(os.path.dirname(os.path.abspath(args.details)), exist_ok=True)
+        with open(args.details, "w") as f:
+            json.dump({"line": line, "details": details}, f, indent=1)
+        line["details_file"] = os.path.relpath(args.details, ROOT)
+    except OSError as e:
+        line["details_file"] = "not written: %s" % e
     print(json.dumps(line))
 
 

@@ -1,0 +1,135 @@
+"""The library's analytical cost model against the hardware: tests/golden/instance_times.json holds the measured
+launch time of every compiled instance on the benchmark shapes (written on an MI355X by
+tests/golden/make_instance_times.py).  The model shares nothing with those numbers, so a wrong constant, a dropped
+term or a sign error in it shows up here as a bad pick or a poor ranking.  Runs on the CPU."""
+import json
+import os
+
+import pytest
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+FIXTURE = os.path.join(HERE, "golden", "instance_times.json")
+
+REGRET_BAR = 0.08        # measured time of the constructed schedule over the measured best instance, per shape
+RANK_BAR = 0.55          # Spearman correlation of predicted with measured times over a shape's instances
+MEAN_RANK_BAR = 0.75     # ... averaged over the shapes
+
+
+@pytest.fixture(scope="module")
+def data():
+    from paper_2502_11407_amd import binding as gs
+    d = json.load(open(FIXTURE))
+    assert d["num_instances"] == gs.num_instances(), "instance list changed: run tests/golden/make_instance_times.py again"
+    return d
+
+
+def _problem(gs, fields):
+    p = gs.Problem()
+    for k, v in fields.items():
+        setattr(p, k, v)
+    return p
+
+
+def _spearman(a, b):
+    def ranks(x):
+        order = sorted(range(len(x)), key=lambda i: x[i])
+        r = [0.0] * len(x)
+        i = 0
+        while i < len(order):
+            j = i
+            while j + 1 < len(order) and x[order[j + 1]] == x[order[i]]:
+                j += 1
+            for k in range(i, j + 1):
+                r[order[k]] = (i + j) / 2.0
+            i = j + 1
+        return r
+    ra, rb = ranks(a), ranks(b)
+    ma, mb = sum(ra) / len(ra), sum(rb) / len(rb)
+    cov = sum((x - ma) * (y - mb) for x, y in zip(ra, rb))
+    va = sum((x - ma) ** 2 for x in ra)
+    vb = sum((y - mb) ** 2 for y in rb)
+    return cov / (va * vb) ** 0.5 if va > 0 and vb > 0 else 1.0
+
+
+def test_fixture_describes_the_compiled_instances(data):
+    from paper_2502_11407_amd import binding as gs
+    for name, sh in data["shapes"].items():
+        p = _problem(gs, sh["problem"])
+        for idx, row in sh["instances"].items():
+            s = gs.instance_schedule(int(idx), p)
+            assert s is not None, (name, idx)
+            got = [s.tile[0][0], s.tile[1][0], s.tile[2][0], s.tile[0][1], s.tile[1][1], s.tile[2][1], s.vthread[0], s.vthread[1]]
+            assert got == row["coords"] and s.stages == row["stages"] and s.direct_lds == row["direct"], (name, idx)
+
+
+def test_constructed_schedule_is_close_to_the_measured_best(data):
+    from paper_2502_11407_amd import binding as gs
+    worst = 0.0
+    for name, sh in data["shapes"].items():
+        p = _problem(gs, sh["problem"])
+        s = gs.construct(p, seed=0, opts=gs.ConstructOpts(0, 0, 0, 0, 0, 0, 1, 0))     # split_k = 1, as measured
+        rows = sh["instances"]
+        assert str(s.kernel_id) in rows, f"{name}: constructed instance {s.kernel_id} was not among the timed ones"
+        best = min(r["us"] for r in rows.values())
+        regret = rows[str(s.kernel_id)]["us"] / best - 1.0
+        print(f"{name}: picked {s.kernel_id} {rows[str(s.kernel_id)]['us']:.1f} us, best {best:.1f} us, regret {100 * regret:.1f} %")
+        assert regret <= REGRET_BAR, (name, s.kernel_id, regret)
+        worst = max(worst, regret)
+    print("worst regret %.1f %%" % (100 * worst))
+
+
+def test_predicted_times_rank_the_instances_like_the_hardware(data):
+    from paper_2502_11407_amd import binding as gs
+    rhos = []
+    for name, sh in data["shapes"].items():
+        p = _problem(gs, sh["problem"])
+        meas, pred = [], []
+        for idx, row in sh["instances"].items():
+            us = gs.predict_us(gs.instance_schedule(int(idx), p), p)
+            assert us > 0, (name, idx)
+            meas.append(row["us"])
+            pred.append(us)
+        if len(meas) < 8:
+            continue
+        rho = _spearman(meas, pred)
+        print(f"{name}: {len(meas)} instances, rank correlation {rho:.2f}")
+        assert rho >= RANK_BAR, (name, rho)
+        rhos.append(rho)
+    assert len(rhos) >= 10 and sum(rhos) / len(rhos) >= MEAN_RANK_BAR
+
+
+def test_predicted_times_are_the_right_size(data):
+    """Absolute scale: over all timed (shape, instance) pairs the prediction is within a factor 2 of the measurement
+    for at least 90 %, and the median ratio is within 25 % of 1."""
+    from paper_2502_11407_amd import binding as gs
+    ratios = []
+    for name, sh in data["shapes"].items():
+        p = _problem(gs, sh["problem"])
+        for idx, row in sh["instances"].items():
+            ratios.append(gs.predict_us(gs.instance_schedule(int(idx), p), p) / row["us"])
+    ratios.sort()
+    inside = sum(1 for r in ratios if 0.5 <= r <= 2.0) / len(ratios)
+    print("pairs", len(ratios), "median ratio %.2f" % ratios[len(ratios) // 2], "within 2x: %.0f %%" % (100 * inside))
+    assert inside >= 0.9 and 0.75 <= ratios[len(ratios) // 2] <= 1.25
+
+
+def test_virtual_threads_measured_and_priced_alike(data):
+    """The plain LDS layout (V = 1) is slower than the conflict-free one on the MFMA-bound shapes, in the measurement
+    and in the model (Eq. 3 as a cost term)."""
+    from paper_2502_11407_amd import binding as gs
+    seen = 0
+    for name in ("cfg2", "cfg3_up", "cfg3_down", "u4"):
+        sh = data["shapes"][name]
+        p = _problem(gs, sh["problem"])
+        rows = sh["instances"]
+        for idx, row in rows.items():
+            c = row["coords"]
+            if c[6] != 1 or c[7] != 1 or not row["direct"]:
+                continue
+            twins = [(j, r) for j, r in rows.items() if r["coords"][:6] == c[:6] and r["direct"] == 1 and r["stages"] == row["stages"]
+                     and r["coords"][6] > 1 and r["coords"][6] == max(q["coords"][6] for q in rows.values() if q["coords"][:6] == c[:6])]
+            for j, full in twins:
+                seen += 1
+                assert row["us"] > 1.03 * full["us"], (name, idx, j)
+                assert gs.predict_us(gs.instance_schedule(int(idx), p), p) > gs.predict_us(gs.instance_schedule(int(j), p), p), (name, idx, j)
+    assert seen >= 6
