@@ -275,6 +275,40 @@ def deep_k_rows(gs, inputs):
     return rows
 
 
+def stream_k_rows(gs, inputs):
+    """The two GPT-2 shapes fill the 256 compute units 1.5 and 0.375 times with 256x256 tiles.  The split-k plan of
+    this library is the hybrid form of stream-K for such counts: whole rounds run one tile per workgroup, the tiles of
+    the partly filled last round are cut along k into equal parts that exchange partial sums.  Rows: every 256x256
+    instance with that plan forced (2 to 4 parts) beside the constructed, unsplit schedule."""
+    import torch
+    rows = []
+    cfgs = inputs.all_configs()
+    for name in ("cfg3_up", "cfg3_down"):
+        wl = cfgs[name]
+        c = Case(gs, inputs, wl)
+        base_ms = c.time_median_ms(batches=3)
+        row = {"workload": wl.name, "constructed": {"kernel_id": c.sched.kernel_id, "split_k": c.sched.split_k, "us": base_ms * 1e3},
+               "forced": []}
+        for idx in range(gs.num_instances()):
+            s = gs.instance_schedule(idx, c.p)
+            if s is None or (s.tile[0][0], s.tile[1][0]) != (256, 256) or (s.direct_lds and wl.K % s.tile[2][0]):
+                continue
+            for split in (2, 3, 4):
+                s.split_k = split
+                if gs.workspace_bytes(c.p, s) == 0:
+                    continue
+                c.sched, c.ws = s, gs.gemm_workspace(c.p, s)
+                ms = c.time_median_ms(batches=3, min_launches=20)
+                row["forced"].append({"kernel_id": idx, "split_k": split, "us": ms * 1e3, "predicted_us": gs.predict_us(s, c.p),
+                                      "workspace_MB": gs.workspace_bytes(c.p, s) / 1e6})
+        row["forced"].sort(key=lambda r: r["us"])
+        row["forced"] = row["forced"][:6]
+        rows.append(row)
+        del c
+        torch.cuda.empty_cache()
+    return rows
+
+
 def operator_table_rows(gs, inputs):
     """The other shapes of the paper's operator table: Conv2d C1-C3 (constructed schedules), GEMV V1-V3 and
     AvgPooling2d P1-P3 (streaming kernels, judged against HBM bandwidth)."""
@@ -420,7 +454,7 @@ def main():
                     help="also launch one plain 256 MiB device copy, the known-size reference for HBM byte counters")
     ap.add_argument("--details", default=os.path.join(ROOT, "gpurun_out", "bench_details.json"),
                     help="file that receives the long sections (the stdout line stays short)")
-    ap.add_argument("--sections", default="operators,unbalanced,deep_k,variants,operator_table,ablation,cpu",
+    ap.add_argument("--sections", default="operators,unbalanced,deep_k,stream_k,variants,operator_table,ablation,cpu",
                     help="comma-separated sections to run besides the headline")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -549,6 +583,9 @@ def main():
     if "deep_k" in sections:
         details["deep_k_gemms"] = deep_k_rows(gs, inputs)
         _progress("deep-k rows done")
+    if "stream_k" in sections:
+        details["stream_k_hybrid"] = stream_k_rows(gs, inputs)
+        _progress("stream-k rows done")
     if "variants" in sections:
         details["variants"] = variant_rows(gs, inputs)
         _progress("output-type variants done")

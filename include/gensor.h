@@ -164,7 +164,8 @@ gensor_status gensor_instance_schedule(int32_t id, const gensor_problem* p, gens
 /*
  * C = alpha * op(A) * op(B) + beta * C          (operator table, GEMM row)
  * A, B: in_dtype, C: out_dtype, row-major with leading dimensions lda, ldb, ldc in
- * elements (lda >= K or M if transA, ldb >= N or K if transB, ldc >= N).
+ * elements (lda >= K, or M if transA: A is then stored [K][M]; ldb >= N, or K if transB: B stored
+ * [N][K]; ldc >= N).
  * s == NULL: a schedule is constructed for `p` (seed 0) and remembered per shape.
  *
  * Split-k (s->split_k > 1).  Tiles are dealt to the compute units in rounds of

@@ -31,8 +31,8 @@ Readings (the paper is silent or garbled here)
   Eq. 2      S = F of the current tile; L, B of the two levels from the hardware table, B per CU
   Eq. 3      W = banks x bank bytes (what the LDS serves per cycle).  x = bytes of bank address space
              spanned by the rows one quarter wave reads together from the operand tile of dimension d:
-             16 rows of min(T_2[k] e, W) bytes for a k-contiguous tile (A always, B when stored [n][k]),
-             else the 4 (16-bit) or 2 (fp32) k rows of an n-contiguous tile, W bytes each.  ceil(x/(V W))
+             16 rows of min(T_2[k] e, W) bytes for a k-contiguous tile (A stored [m][k], B stored [n][k]),
+             else the 4 (16-bit) or 2 (fp32) k rows of an n- or m-contiguous tile, W bytes each.  ceil(x/(V W))
              of those rows share a bank when the tile is interleaved over V phases.  setVThread doubles V
              up to ceil(x/W) (conflict-free) and then wraps to 1; benefit = ceil(x/(V W)) / ceil(x/(V' W))
   T, t       Algorithm 1 halves one temperature T per step and stops at the threshold.  The
@@ -97,6 +97,7 @@ class View:
     bsrc: int = 0       # 0 k-contiguous B, 1 n-contiguous B, 2 convolution gather, 3 n-contiguous B sampled at stride 2
     conv: Optional[Tuple[int, ...]] = None   # convolution geometry (n, c, h, w, r, s, stride, pad), else None
     prepass: int = 0    # 1: a strided pointwise convolution (its input is compacted by a pre-pass kernel)
+    asrc: int = 0       # 0 k-contiguous A (stored [m][k]), 1 m-contiguous A (stored [k][m])
 
 
 @dataclass
@@ -174,7 +175,7 @@ def mfma_block(view: View, s: State) -> int:
 def conflict_ways(view: View, hw: "Hw", bk: int, d: int, v: int) -> int:
     """Eq. 3's ceil(x / (V W)) for the operand tile of dimension d (0: m x k, 1: k x n)."""
     W = hw.lds_banks * hw.lds_bank_bytes
-    if d == DIM_M or view.bsrc == 0:
+    if (view.asrc == 0) if d == DIM_M else (view.bsrc == 0):
         x = 16 * min(bk * view.e, W)
     else:
         x = (4 if view.e == 2 else 2) * W

@@ -65,13 +65,13 @@ def generate():
     for d in L:
         es = 4 if d["dt"] == "f32" else 2
         kg = (64 // d["mb"]) * (16 // es)
-        a_bytes = d["bm"] * d["bk"] * es
+        a_bytes = d["bm"] * d["bk"] * es if d["asrc"] == "KC" else d["bk"] * (d["bm"] * es + lattice.pad_m(d))
         b_bytes = d["bn"] * d["bk"] * es if (d["bsrc"] == "KC" or d["direct"]) else d["bk"] * (d["bn"] * es + lattice.pad_n(d))
         lds = 0 if d["units"] else (a_bytes + b_bytes) * d["stages"]
         threads = (d["bm"] // d["wm"]) * (d["bn"] // d["wn"]) * 64
-        reg.append("  {%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, launch_%d, %s}," % (
+        reg.append("  {%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, launch_%d, %s}," % (
             d["id"], lattice.DT[d["dt"]], lattice.DT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"],
-            d["vm"], d["vn"], lattice.BSRC[d["bsrc"]], d["vec"], d["stages"], d["direct"], lds, threads, kg, d["units"], d["id"],
+            d["vm"], d["vn"], lattice.BSRC[d["bsrc"]], lattice.ASRC[d["asrc"]], d["vec"], d["stages"], d["direct"], lds, threads, kg, d["units"], d["id"],
             ("launch_split_%d" % d["id"]) if lattice.splittable(d) else "nullptr"))
     reg.append("};")
     reg.append("const int g_num_instances = %d;" % len(L))

@@ -15,7 +15,7 @@
 //   * Eq. 3 -- W = banks * bank bytes, what the LDS serves per cycle.  x = the bytes of bank address
 //     space spanned by the rows that one quarter wave reads together from the operand tile of
 //     dimension d: 16 rows of min(T_2[k] e, W) bytes for a k-contiguous tile, the 4 (16-bit) or 2
-//     (fp32) k rows of an n-contiguous tile at W each.  ceil(x / (V W)) of those rows share a bank
+//     (fp32) k rows of an n-contiguous B (or m-contiguous A) tile at W each.  ceil(x / (V W)) of those rows share a bank
 //     when the tile is interleaved over V phases (V = 1: the plain layout).  setVThread doubles V
 //     up to ceil(x / W), where the reads are conflict-free, then wraps to 1; the benefit is the
 //     ratio of the conflict ways before and after, so the wrap has a (small) positive benefit.
@@ -119,7 +119,7 @@ int mfma_block(const Ctx& c, const Etir& e) { return e.tile[2][1] == c.g ? 32 : 
 // of a workgroup tile of k depth bk whose rows are interleaved over v phases.
 int conflict_ways(const GemmView& view, const gensor_hw& hw, int bk, int d, int v) {
   const int W = hw.lds_banks * hw.lds_bank_bytes;
-  const bool k_contiguous = d == 0 || view.bsrc == B_KC;
+  const bool k_contiguous = d == 0 ? view.asrc == A_KC : view.bsrc == B_KC;
   const int row_bytes = bk * view.esize;
   const int x = k_contiguous ? 16 * (row_bytes < W ? row_bytes : W) : (view.esize == 2 ? 4 : 2) * W;
   return (x + v * W - 1) / (v * W);
@@ -531,7 +531,7 @@ extern "C" gensor_status gensor_construct(const gensor_problem* p, const gensor_
   if (st != GENSOR_OK) return st;
   const int epc = 16 / v.esize;
   bool vec_ok = true;
-  if (v.bsrc != B_CONV) vec_ok = v.K % epc == 0 && (v.bsrc == B_KC || v.N % epc == 0);
+  if (v.bsrc != B_CONV) vec_ok = (v.asrc == A_KC ? v.K : v.M) % epc == 0 && (v.bsrc == B_KC ? v.K : v.N) % epc == 0;
   return construct_internal(p, hw, opts, seed, vec_ok, VIEW_DEFAULT, out);
 }
 

@@ -14,7 +14,8 @@
 //   VEC        global accesses are 16-byte vectors (true) or single elements (false)
 //   DIRECT     K-contiguous operands go global->LDS without passing through registers
 //
-// Operand sources.  A (the m x k operand) is always k-contiguous: A[m][k].  B is
+// Operand sources.  A (the m x k operand) is k-contiguous, A[m][k] (A_KC), or m-contiguous, A stored
+// [k][m] (A_MC, "transA": staged and read exactly like an n-contiguous B, register-staged only).  B is
 //   KC   k-contiguous,  B stored [n][k]   (column-major B / "transB")
 //   NC   n-contiguous,  B stored [k][n]   (row-major B)
 //   CONV n = (image, out row, out col), k = (channel, filter row, filter col): element
@@ -45,6 +46,7 @@ namespace gensor {
 // B_NCS2: n-contiguous B whose column n = p*Q + q is read at (2p)*W + 2q of a plane of H*W elements
 // (= ldb): the input of a pointwise convolution with stride 2, sampled while it is fetched.
 enum BSrc { B_KC = 0, B_NC = 1, B_CONV = 2, B_NCS2 = 3 };
+enum ASrc { A_KC = 0, A_MC = 1 };
 
 struct KernelArgs {
   const void* A;
@@ -157,12 +159,12 @@ template <> struct Mfma<f32_t, 16> {   // 16x16x4 per step
 
 // ---------------------------------------------------------------- schedule -> constants
 template <typename T_, typename OutT_, int BM_, int BN_, int BK_, int WM_, int WN_, int MB_, int VM_, int VN_,
-          int BSRC_, bool VEC_, int STAGES_, bool DIRECT_>
+          int BSRC_, bool VEC_, int STAGES_, bool DIRECT_, int ASRC_ = A_KC>
 struct Cfg {
   typedef T_ T;
   typedef OutT_ OutT;
   static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MB = MB_, VM = VM_, VN = VN_;
-  static constexpr int BSRC = BSRC_, STAGES = STAGES_;
+  static constexpr int BSRC = BSRC_, STAGES = STAGES_, ASRC = ASRC_;
   static constexpr bool VEC = VEC_, DIRECT = DIRECT_;
   static constexpr int ES = ElemSize<T>::value;
   static constexpr int EPC = 16 / ES;                        // elements per 16-byte chunk
@@ -186,17 +188,22 @@ struct Cfg {
   static constexpr int PAD_T = (VN >= 4) ? 64 : 32;
   static constexpr int PAD_N = (VN == 1) ? 0 : (PAD_T + 2 * PAD_T - (BN * ES) % (2 * PAD_T)) % (2 * PAD_T);
   static constexpr int PITCH_N = NC_DIRECT ? BN * ES : BN * ES + PAD_N;
-  static constexpr int A_BYTES = BM * PITCH_K;
+  // m-contiguous A tile: [BK][BM] + pad, the same rule
+  static constexpr int PAD_TM = (VM >= 4) ? 64 : 32;
+  static constexpr int PAD_M = (VM == 1) ? 0 : (PAD_TM + 2 * PAD_TM - (BM * ES) % (2 * PAD_TM)) % (2 * PAD_TM);
+  static constexpr int PITCH_M = BM * ES + PAD_M;
+  static constexpr int A_BYTES = (ASRC == A_KC) ? BM * PITCH_K : BK * PITCH_M;
   static constexpr int B_BYTES = (BSRC == B_KC) ? BN * PITCH_K : BK * PITCH_N;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = STAGE_BYTES * STAGES;
-  static constexpr int A_CHUNKS = BM * CPR;
+  static constexpr int A_CHUNKS = (ASRC == A_KC) ? BM * CPR : BK * (BM * ES / 16);
   static constexpr int B_CHUNKS = (BSRC == B_KC) ? BN * CPR : BK * (BN * ES / 16);
   static constexpr int A_LOADS = (A_CHUNKS + THREADS - 1) / THREADS;
   static constexpr int B_LOADS = (B_CHUNKS + THREADS - 1) / THREADS;
   static_assert(BM % WM == 0 && BN % WN == 0, "wave tile must divide workgroup tile");
   static_assert(WM % MB == 0 && WN % MB == 0, "wave tiles are whole MFMA blocks");
-  static_assert(VM >= 1 && (VM & (VM - 1)) == 0 && VM <= V_MAX_K, "V of the m operand: a power of two up to the chunks per row");
+  static_assert(VM >= 1 && (VM & (VM - 1)) == 0 && VM <= (ASRC == A_KC ? V_MAX_K : V_MAX_N), "V of the m operand: a power of two up to the chunks per row");
+  static_assert(ASRC == A_KC || (!DIRECT_ && BSRC != B_CONV && BSRC != B_NCS2), "an m-contiguous A is register-staged, GEMM only");
   static_assert(VN >= 1 && (VN & (VN - 1)) == 0 && VN <= (BSRC == B_KC ? V_MAX_K : V_MAX_N), "V of the n operand");
   static_assert(BK % KG == 0, "BK must be a multiple of the fragment k extent");
   static_assert(MB == 32 || MB == 16, "MFMA block edge");
@@ -284,7 +291,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     k_first = (int64_t)kt0 * BK;
     Kx = min(args.K, kt1 * BK) - kt0 * BK;
   }
-  const char* Ab = (const char*)args.A + ((int64_t)bidx * args.strideA + k_first) * ES;
+  const char* Ab = (const char*)args.A + ((int64_t)bidx * args.strideA + (C::ASRC == A_KC ? k_first : k_first * args.lda)) * ES;
   const char* Bb = (const char*)args.B + ((int64_t)bidx * args.strideB + (C::BSRC == B_KC ? k_first : k_first * args.ldb)) * ES;
 
   // ---- accumulators
@@ -308,11 +315,15 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   };
   const int rows_valid = min(BM, args.M - m0);
   const int cols_valid = min(BN, args.N - n0);
-  const char* a_tile = Ab + (int64_t)m0 * args.lda * ES;
+  const char* a_tile = (C::ASRC == A_KC) ? Ab + (int64_t)m0 * args.lda * ES : Ab + (int64_t)m0 * ES;
   const char* b_tile = (C::BSRC == B_KC) ? Bb + (int64_t)n0 * args.ldb * ES : (C::BSRC == B_NCS2 ? Bb : Bb + (int64_t)n0 * ES);
   auto rsrc_a = [&](int k0) {
-    return __builtin_amdgcn_make_buffer_rsrc((void*)(a_tile + (int64_t)k0 * ES), 0,
-        clamp_records(((int64_t)(rows_valid - 1) * args.lda + (Kx - k0)) * ES), RSRC_FLAGS);
+    if constexpr (C::ASRC == A_KC)
+      return __builtin_amdgcn_make_buffer_rsrc((void*)(a_tile + (int64_t)k0 * ES), 0,
+          clamp_records(((int64_t)(rows_valid - 1) * args.lda + (Kx - k0)) * ES), RSRC_FLAGS);
+    else      // k rows beyond K fall out of range; rows of the tile beyond M read what follows them and are never stored
+      return __builtin_amdgcn_make_buffer_rsrc((void*)(a_tile + (int64_t)k0 * args.lda * ES), 0,
+          clamp_records(((int64_t)(Kx - k0 - 1) * args.lda + (args.M - m0)) * ES), RSRC_FLAGS);
   };
   auto rsrc_b = [&](int k0) {
     if constexpr (C::BSRC == B_KC)
@@ -336,9 +347,15 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 #pragma unroll
   for (int i = 0; i < C::A_LOADS; ++i) {
     const int q = tid + i * C::THREADS;
-    const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::VM);
-    a_voff[i] = (uint32_t)((row * (int)args.lda + ch * EPC) * ES);
-    a_kch[i] = ch * EPC;
+    if constexpr (C::ASRC == A_KC) {
+      const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::VM);
+      a_voff[i] = (uint32_t)((row * (int)args.lda + ch * EPC) * ES);
+      a_kch[i] = ch * EPC;
+    } else {
+      constexpr int CPRM = BM * ES / 16;
+      a_voff[i] = (uint32_t)(((q / CPRM) * (int)args.lda + (q % CPRM) * EPC) * ES);
+      a_kch[i] = q / CPRM;
+    }
   }
   uint32_t b_voff[C::B_LOADS], b_kch[C::B_LOADS];
   uint32_t b_voff2[C::BSRC == B_NCS2 ? C::B_LOADS : 1];      // second half of a sampled chunk
@@ -377,7 +394,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   // element-wise access for the scalar path and the convolution gather
   auto a_elem_bits = [&](int row, int k) -> uint32_t {
     if (row < args.M && k < Kx) {
-      int64_t idx = (int64_t)row * args.lda + k;
+      int64_t idx = (C::ASRC == A_KC) ? (int64_t)row * args.lda + k : (int64_t)k * args.lda + row;
       if constexpr (ES == 4) return ((const uint32_t*)Ab)[idx];
       else return ((const uint16_t*)Ab)[idx];
     }
@@ -422,8 +439,13 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       for (int i = 0; i < C::A_LOADS; ++i) {
         const int q = tid + i * C::THREADS;
         if (C::A_CHUNKS % C::THREADS != 0 && q >= C::A_CHUNKS) break;
-        const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::VM);
-        ra[i] = pack_chunk([&](int e) { return a_elem_bits(m0 + row, k0 + ch * EPC + e); });
+        if constexpr (C::ASRC == A_KC) {
+          const int row = q / C::CPR, ch = swizzled_chunk(row, q % C::CPR, C::RPP, C::VM);
+          ra[i] = pack_chunk([&](int e) { return a_elem_bits(m0 + row, k0 + ch * EPC + e); });
+        } else {
+          constexpr int CPRM = BM * ES / 16;
+          ra[i] = pack_chunk([&](int e) { return a_elem_bits(m0 + (q % CPRM) * EPC + e, k0 + q / CPRM); });
+        }
       }
     } else {
       const __amdgpu_buffer_rsrc_t r = rsrc_a(k0);
@@ -432,7 +454,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         if (C::A_CHUNKS % C::THREADS != 0 && tid + i * C::THREADS >= C::A_CHUNKS) break;
         if (i * parts < part * C::A_LOADS || i * parts >= (part + 1) * C::A_LOADS) continue;
         // (direct staging is only launched for K a multiple of BK: every tile is full)
-        const uint32_t off = (C::DIRECT || full || (int)a_kch[i] < Kx - k0) ? a_voff[i] : OOB;
+        const uint32_t off = (C::ASRC == A_MC || C::DIRECT || full || (int)a_kch[i] < Kx - k0) ? a_voff[i] : OOB;
         if constexpr (C::DIRECT)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (GENSOR_LDS void*)(lds + st * C::STAGE_BYTES + (i * C::THREADS + wave * 64) * 16),
                                                    16, off, 0, 0, 0);
@@ -486,7 +508,12 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       for (int i = 0; i < C::A_LOADS; ++i) {
         const int q = tid + i * C::THREADS;
         if (C::A_CHUNKS % C::THREADS != 0 && q >= C::A_CHUNKS) break;
-        *(GENSOR_LDS u32x4*)(abase + q * 16) = ra[i];
+        if constexpr (C::ASRC == A_KC) {
+          *(GENSOR_LDS u32x4*)(abase + q * 16) = ra[i];
+        } else {
+          constexpr int CPRM = BM * ES / 16;
+          *(GENSOR_LDS u32x4*)(abase + (q / CPRM) * C::PITCH_M + (q % CPRM) * 16) = ra[i];
+        }
       }
 #pragma unroll
       for (int i = 0; i < C::B_LOADS; ++i) {
@@ -533,53 +560,63 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   constexpr bool DEEP = C::DIRECT && C::STAGES == 2 && C::KSTEPS == 4 && C::MBLK * C::NBLK >= 16;
   constexpr int FSETS = DEEP ? 4 : 2;
   u32x4 fa[FSETS][C::MBLK], fb[FSETS][C::NBLK];
+  // Fragment of one MFMA block from a tile stored [k][rows] (an n-contiguous B or an m-contiguous A), `first` =
+  // the block's first row/column inside the tile, `direct` = the tile is unpadded and XOR-swizzled.
+  auto read_transposed = [&](GENSOR_LDS char* base, int pitch, int first, int ks, auto direct_tag, int v) -> u32x4 {
+    constexpr bool direct = decltype(direct_tag)::value;
+    if constexpr (ES == 4) {
+      // fp32: element t of this lane's chunk is k = ks*KG + fgrp*4 + t
+      const int col = first + frow;
+      u32x4 r;
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        const int kr = ks * C::KG + fgrp * 4 + tt;
+        const int cb = direct ? ((col * 4) ^ nc_swizzle(kr, v)) : col * 4;
+        r[tt] = *(GENSOR_LDS uint32_t*)(base + kr * pitch + cb);
+      }
+      return r;
+    } else {
+      // 16-bit: two transposing reads.  In each 16-lane group, lane s fetches 4 consecutive rows/columns of
+      // k row (s/4) and receives, for row/column s, the 4 consecutive k of the group's k rows.
+      const int g = lane >> 4, s = lane & 15;
+      int krow, col;
+      if constexpr (MB == 32) {    // groups: (g%2) picks the 16-wide half, (g/2) the 8-deep k half
+        krow = ks * C::KG + (g >> 1) * 8 + (s >> 2);
+        col = first + (g & 1) * 16 + (s & 3) * 4;
+      } else {                     // 16x16 blocks: group g holds k = 8g..8g+7
+        krow = ks * C::KG + g * 8 + (s >> 2);
+        col = first + (s & 3) * 4;
+      }
+      const int cb0 = direct ? ((col * 2) ^ nc_swizzle(krow, v)) : col * 2;
+      const int cb1 = direct ? ((col * 2) ^ nc_swizzle(krow + 4, v)) : col * 2;
+      GENSOR_LDS char* p = base + krow * pitch;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + cb0));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + 4 * pitch + cb1));
+      u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+      u32x4 r = {l2[0], l2[1], h2[0], h2[1]};
+      return r;
+    }
+  };
   auto read_frags = [&](int st, int ks, int buf) {
     GENSOR_LDS char* abase = lds + st * C::STAGE_BYTES;
     GENSOR_LDS char* bbase = abase + C::A_BYTES;
     const int ch = ks * C::LANE_GROUPS + fgrp;
 #pragma unroll
     for (int bi = 0; bi < C::MBLK; ++bi) {
-      const int row = block_row(bi) + frow;
-      fa[buf][bi] = *(GENSOR_LDS u32x4*)(abase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::VM) * 16);
+      if constexpr (C::ASRC == A_KC) {
+        const int row = block_row(bi) + frow;
+        fa[buf][bi] = *(GENSOR_LDS u32x4*)(abase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::VM) * 16);
+      } else {
+        fa[buf][bi] = read_transposed(abase, C::PITCH_M, block_row(bi), ks, std::false_type{}, C::VM);
+      }
     }
 #pragma unroll
     for (int bj = 0; bj < C::NBLK; ++bj) {
       if constexpr (C::BSRC == B_KC) {
         const int row = block_col(bj) + frow;
         fb[buf][bj] = *(GENSOR_LDS u32x4*)(bbase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::VN) * 16);
-      } else if constexpr (ES == 4) {
-        // fp32, [k][n] tile: element t of this lane's chunk is k = ks*KG + fgrp*4 + t
-        const int col = block_col(bj) + frow;
-        u32x4 v;
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt)
-        {
-          const int kr = ks * C::KG + fgrp * 4 + tt;
-          const int cb = C::NC_DIRECT ? ((col * 4) ^ nc_swizzle(kr, C::VN)) : col * 4;
-          v[tt] = *(GENSOR_LDS uint32_t*)(bbase + kr * C::PITCH_N + cb);
-        }
-        fb[buf][bj] = v;
       } else {
-        // 16-bit, [k][n] tile: two transposing reads.  In each 16-lane group, lane s
-        // fetches 4 consecutive n of row (s/4) and receives, for column s, the 4
-        // consecutive k of the group's rows.
-        const int g = lane >> 4, s = lane & 15;
-        int krow, col;
-        if constexpr (MB == 32) {    // groups: (g%2) picks the 16-column half, (g/2) the 8-deep k half
-          krow = ks * C::KG + (g >> 1) * 8 + (s >> 2);
-          col = block_col(bj) + (g & 1) * 16 + (s & 3) * 4;
-        } else {                     // 16x16 blocks: group g holds k = 8g..8g+7
-          krow = ks * C::KG + g * 8 + (s >> 2);
-          col = block_col(bj) + (s & 3) * 4;
-        }
-        const int cb0 = C::NC_DIRECT ? ((col * 2) ^ nc_swizzle(krow, C::VN)) : col * 2;
-        const int cb1 = C::NC_DIRECT ? ((col * 2) ^ nc_swizzle(krow + 4, C::VN)) : col * 2;
-        GENSOR_LDS char* p = bbase + krow * C::PITCH_N;
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + cb0));
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GENSOR_LDS s16x4*)(p + 4 * C::PITCH_N + cb1));
-        u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-        u32x4 v = {l2[0], l2[1], h2[0], h2[1]};
-        fb[buf][bj] = v;
+        fb[buf][bj] = read_transposed(bbase, C::PITCH_N, block_col(bj), ks, std::integral_constant<bool, C::NC_DIRECT>{}, C::VN);
       }
     }
   };
@@ -596,7 +633,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   // groups in front of each MFMA of this step, so that they complete under matrix work.
   auto interleave = [&]() {
     constexpr int NM = C::MBLK * C::NBLK * (ES == 4 ? 4 : 1);
-    constexpr int NR = C::MBLK + C::NBLK * (C::BSRC == B_KC ? 1 : (ES == 4 ? 4 : 2));
+    constexpr int NR = C::MBLK * (C::ASRC == A_KC ? 1 : (ES == 4 ? 4 : 2)) + C::NBLK * (C::BSRC == B_KC ? 1 : (ES == 4 ? 4 : 2));
     constexpr int RPM = (NR + NM - 1) / NM;
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
@@ -613,7 +650,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   auto interleave_vmem = [&](auto separate_tag) {
     constexpr bool separate = decltype(separate_tag)::value;
     constexpr int NM = C::MBLK * C::NBLK * (ES == 4 ? 4 : 1);
-    constexpr int NR = C::MBLK + C::NBLK * (C::BSRC == B_KC ? 1 : (ES == 4 ? 4 : 2));
+    constexpr int NR = C::MBLK * (C::ASRC == A_KC ? 1 : (ES == 4 ? 4 : 2)) + C::NBLK * (C::BSRC == B_KC ? 1 : (ES == 4 ? 4 : 2));
     constexpr int RPM = (NR + NM - 1) / NM;
     constexpr int READ_SLOTS = (NR + RPM - 1) / RPM;
 #pragma unroll

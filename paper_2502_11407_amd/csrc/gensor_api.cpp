@@ -44,10 +44,10 @@ gensor_status gemm_view(const gensor_problem* p, GemmView* v, int mode) {
     if (p->M <= 0 || p->N <= 0 || p->K <= 0) return GENSOR_ERR_INVALID_ARG;
     if (p->op == GENSOR_OP_BMM && p->batch <= 0) return GENSOR_ERR_INVALID_ARG;
     if ((p->transA != 0 && p->transA != 1) || (p->transB != 0 && p->transB != 1)) return GENSOR_ERR_INVALID_ARG;
-    if (p->transA) return GENSOR_ERR_UNSUPPORTED;     // A must be k-contiguous
     v->M = p->M; v->N = p->N; v->K = p->K;
     v->batch = p->op == GENSOR_OP_BMM ? p->batch : 1;
     v->bsrc = p->transB ? B_KC : B_NC;
+    v->asrc = p->transA ? A_MC : A_KC;
   } else if (p->op == GENSOR_OP_CONV2D) {
     if (p->n <= 0 || p->c <= 0 || p->h <= 0 || p->w <= 0 || p->k <= 0 || p->r <= 0 || p->s <= 0) return GENSOR_ERR_INVALID_ARG;
     if (p->stride <= 0 || p->pad < 0) return GENSOR_ERR_INVALID_ARG;
@@ -130,7 +130,7 @@ bool conv_patch_plan(const InstanceDesc& d, const GemmView& v, ConvPlan* plan) {
 }
 
 bool instance_serves(const InstanceDesc& d, const GemmView& v) {
-  if (d.in_dtype != v.in_dtype || d.out_dtype != v.out_dtype || d.bsrc != v.bsrc) return false;
+  if (d.in_dtype != v.in_dtype || d.out_dtype != v.out_dtype || d.bsrc != v.bsrc || d.asrc != v.asrc) return false;
   if (d.units) return conv_patch_plan(d, v, nullptr);
   return true;
 }
@@ -158,7 +158,8 @@ const InstanceDesc* find_instance(const gensor_schedule* s, const GemmView& v) {
 bool vector_ok(const GemmView& v, const void* A, int64_t lda, int64_t strideA, const void* B, int64_t ldb, int64_t strideB) {
   const int epc = 16 / v.esize;
   auto al = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
-  if (!al(A) || lda % epc || strideA % epc || v.K % epc) return false;
+  if (!al(A) || lda % epc || strideA % epc || (v.asrc == A_KC ? v.K : v.M) % epc) return false;
+  if (v.asrc == A_MC && v.bsrc == B_KC && v.K % epc) return false;
   if (v.bsrc == B_KC) return al(B) && ldb % epc == 0 && strideB % epc == 0;
   if (v.bsrc == B_NC || v.bsrc == B_NCS2) return al(B) && ldb % epc == 0 && strideB % epc == 0 && v.N % epc == 0;
   return al(B);  // convolution: the gather is element-wise; the patch path reads 16-byte vectors
@@ -238,7 +239,7 @@ std::map<std::tuple<int, int, int, int, int, int64_t, int64_t, int64_t, int64_t,
 const size_t kMemoLimit = 4096;      // shapes remembered; a full memo is emptied (a shape seen again is constructed again)
 
 gensor_status memoised_schedule(const gensor_problem* p, bool vec_ok, int view_mode, bool no_split, gensor_schedule* out) {
-  auto key = std::make_tuple((int)p->op, (int)p->in_dtype, (int)p->out_dtype, (int)p->transB,
+  auto key = std::make_tuple((int)p->op, (int)p->in_dtype, (int)p->out_dtype, (int)p->transB + 2 * (int)p->transA,
                              (vec_ok ? 1 : 0) + (no_split ? 2 : 0) + 4 * view_mode,
                              p->op == GENSOR_OP_CONV2D ? p->n : p->batch, p->op == GENSOR_OP_CONV2D ? p->c : p->M,
                              p->op == GENSOR_OP_CONV2D ? p->h : p->N, p->op == GENSOR_OP_CONV2D ? p->w : p->K,
@@ -288,7 +289,8 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
   if (sp.split > 1 && (!ws_aligned || workspace_bytes < sp.bytes)) return GENSOR_ERR_WORKSPACE;
   // 32-bit offsets inside one workgroup tile
   const int64_t lim = 0x7fffffffll;
-  if ((int64_t)(d->bm + 1) * lda * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
+  if (v.asrc == A_KC && (int64_t)(d->bm + 1) * lda * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
+  if (v.asrc == A_MC && ((int64_t)(d->bk + 1) * lda + d->bm) * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
   // (the convolution epilogues address the output with 64-bit indices and never use ldc)
   if (v.bsrc != B_CONV && (int64_t)(d->bm + 1) * ldc * v.osize >= lim) return GENSOR_ERR_UNSUPPORTED;
   if (v.bsrc == B_KC && (int64_t)(d->bn + 1) * ldb * v.esize >= lim) return GENSOR_ERR_UNSUPPORTED;
@@ -342,7 +344,7 @@ extern "C" gensor_status gensor_bmm(const gensor_schedule* s, const gensor_probl
   GemmView v;
   gensor_status st = gemm_view(p, &v);
   if (st != GENSOR_OK) return st;
-  if (lda < v.K) return GENSOR_ERR_INVALID_ARG;
+  if (lda < (v.asrc == A_KC ? v.K : v.M)) return GENSOR_ERR_INVALID_ARG;
   if (ldb < (v.bsrc == B_KC ? v.K : v.N)) return GENSOR_ERR_INVALID_ARG;
   if (ldc < v.N) return GENSOR_ERR_INVALID_ARG;
   if (strideA < 0 || strideB < 0 || strideC < 0) return GENSOR_ERR_INVALID_ARG;

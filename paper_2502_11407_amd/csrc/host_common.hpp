@@ -13,6 +13,7 @@ struct GemmView {
   int64_t P, Q;          // convolution output extent
   int in_dtype, out_dtype, esize, osize;
   int bsrc;              // BSrc
+  int asrc;              // ASrc: A stored [m][k] (A_KC) or [k][m] (A_MC, transA)
   int pointwise;         // convolution with a 1x1 filter and no padding, viewed as one GEMM per image
   // convolution geometry (zero otherwise)
   int64_t cn, cc, ch, cw, cr, cs, cstride, cpad;

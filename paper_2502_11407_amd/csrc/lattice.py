@@ -5,22 +5,24 @@ from itertools import product
 
 DT = {"f32": 0, "f16": 1, "bf16": 2}
 BSRC = {"KC": 0, "NC": 1, "CONV": 2, "NCS2": 3}
+ASRC = {"KC": 0, "MC": 1}
 CT = {"f32": "f32_t", "f16": "f16_t", "bf16": "bf16_t"}
 
 
-def full_v(dt, bk, bsrc):
+def full_v(dt, bk, bsrc, asrc="KC"):
     """Virtual threads at which the fragment reads of both operand tiles are free of bank conflicts: a
     k-contiguous tile needs as many phases as it has 16-byte chunks per row; an n-contiguous one has its
     4 (16-bit) or 2 (fp32) k rows that are read together spread by the row pad."""
     es = 4 if dt == "f32" else 2
     cpr = bk * es // 16
-    return cpr, (cpr if bsrc == "KC" else (2 if dt == "f32" else 4))
+    strided = 2 if dt == "f32" else 4
+    return (cpr if asrc == "KC" else strided), (cpr if bsrc == "KC" else strided)
 
 
-def _inst(dt, out, bm, bn, bk, wm, wn, mb, vm=None, vn=None, bsrc="KC", vec=1, stages=2, direct=0, units=0):
-    fm, fn = (1, 1) if units else full_v(dt, bk, bsrc)
+def _inst(dt, out, bm, bn, bk, wm, wn, mb, vm=None, vn=None, bsrc="KC", vec=1, stages=2, direct=0, units=0, asrc="KC"):
+    fm, fn = (1, 1) if units else full_v(dt, bk, bsrc, asrc)
     return dict(dt=dt, out=out, bm=bm, bn=bn, bk=bk, wm=wm, wn=wn, mb=mb, vm=vm or fm, vn=vn or fn,
-                bsrc=bsrc, vec=vec, stages=stages, direct=direct, units=units)
+                bsrc=bsrc, vec=vec, stages=stages, direct=direct, units=units, asrc=asrc)
 
 
 def _convp(dt, out, bm, bn, bkc, wm, wn, units, stages=2):
@@ -30,13 +32,21 @@ def _convp(dt, out, bm, bn, bkc, wm, wn, units, stages=2):
     return _inst(dt, out, bm, bn, bkc, wm, wn, 32, 1, 1, "CONV", 1, stages, 1, units)
 
 
+def _pad(v, row_bytes):
+    if v == 1:
+        return 0
+    t = 64 if v >= 4 else 32
+    return (3 * t - row_bytes % (2 * t)) % (2 * t)
+
+
 def pad_n(d):
     """Row pad in bytes of a register-staged n-contiguous B tile (the kernel's PAD_N)."""
-    es = 4 if d["dt"] == "f32" else 2
-    if d["vn"] == 1:
-        return 0
-    t = 64 if d["vn"] >= 4 else 32
-    return (3 * t - (d["bn"] * es) % (2 * t)) % (2 * t)
+    return _pad(d["vn"], d["bn"] * (4 if d["dt"] == "f32" else 2))
+
+
+def pad_m(d):
+    """Row pad in bytes of an m-contiguous A tile (the kernel's PAD_M)."""
+    return _pad(d["vm"], d["bm"] * (4 if d["dt"] == "f32" else 2))
 
 
 def splittable(d):
@@ -157,10 +167,25 @@ def lattice():
         out.append(_inst("f32", "f32", 32, 32, 32, 16, 16, 16, 1, 1, bsrc))
     out.append(_inst("f16", "f32", 256, 256, 64, 128, 64, 32, 1, 1, "NCS2"))
     out.append(_inst("f16", "f32", 128, 128, 64, 64, 64, 32, 1, 1, "CONV"))
+    # A stored [k][m] (transA): register-staged instances, both B layouts
+    for bsrc in ("KC", "NC"):
+        for dt in ("f16", "bf16"):
+            for (bm, bn, wm, wn, mb) in ((256, 256, 128, 64, 32), (256, 128, 64, 64, 32), (128, 256, 64, 64, 32), (128, 128, 64, 64, 32),
+                                         (128, 128, 64, 64, 16), (64, 64, 32, 32, 32), (32, 32, 16, 16, 16)):
+                out.append(_inst(dt, "f32", bm, bn, 64, wm, wn, mb, bsrc=bsrc, asrc="MC"))
+            out.append(_inst(dt, "f32", 128, 128, 32, 64, 64, 32, bsrc=bsrc, asrc="MC"))
+            out.append(_inst(dt, "f32", 128, 128, 64, 64, 64, 32, 1, 1, bsrc=bsrc, asrc="MC"))
+            out.append(_inst(dt, "f32", 64, 64, 32, 32, 32, 16, bsrc=bsrc, vec=0, asrc="MC"))
+            out.append(_inst(dt, dt, 128, 128, 64, 64, 64, 32, bsrc=bsrc, asrc="MC"))
+            out.append(_inst(dt, dt, 64, 64, 32, 32, 32, 16, bsrc=bsrc, vec=0, asrc="MC"))
+        for (bm, bn, wm, wn, mb) in ((128, 128, 64, 64, 32), (64, 64, 32, 32, 32), (64, 64, 32, 32, 16), (32, 32, 16, 16, 16)):
+            out.append(_inst("f32", "f32", bm, bn, 32, wm, wn, mb, bsrc=bsrc, asrc="MC"))
+        out.append(_inst("f32", "f32", 64, 64, 32, 32, 32, 32, 1, 1, bsrc=bsrc, asrc="MC"))
+        out.append(_inst("f32", "f32", 64, 64, 16, 32, 32, 16, bsrc=bsrc, vec=0, asrc="MC"))
     for i, d in enumerate(out):
         d["id"] = i
     keys = [(d["dt"], d["out"], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"], d["vm"], d["vn"], d["bsrc"], d["vec"],
-             d["stages"], d["direct"], d["units"]) for d in out]
+             d["stages"], d["direct"], d["units"], d["asrc"]) for d in out]
     assert len(set(keys)) == len(keys), "duplicate instance"
     return out
 
@@ -169,9 +194,9 @@ def cfg_type(d):
     if d["units"]:
         return "ConvCfg<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d>" % (
             CT[d["dt"]], CT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"], d["units"], d["stages"])
-    return ("Cfg<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s, %d, %s>" % (
+    return ("Cfg<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d, %d, %s, %d, %s, %d>" % (
         CT[d["dt"]], CT[d["out"]], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"], d["vm"], d["vn"],
-        BSRC[d["bsrc"]], "true" if d["vec"] else "false", d["stages"], "true" if d["direct"] else "false"))
+        BSRC[d["bsrc"]], "true" if d["vec"] else "false", d["stages"], "true" if d["direct"] else "false", ASRC[d["asrc"]]))
 
 
 if __name__ == "__main__":

@@ -16,6 +16,7 @@ struct InstanceDesc {
   int in_dtype, out_dtype;              // gensor_dtype values
   int bm, bn, bk, wm, wn, mb, vm, vn;
   int bsrc;                             // BSrc
+  int asrc;                             // ASrc
   int vec, stages, direct;
   int lds_bytes, threads, kg;           // kg: k consumed per fragment read (lds_bytes 0: set per problem)
   int units;                            // patch-staged convolution: transpose units per thread

@@ -294,6 +294,9 @@ def _views():
          oc.View(40, 4 * 7 * 6, 24 * 6, 1, 4, 4, 2, conv=(4, 24, 13, 11, 3, 2, 2, 1))),
         (gs.gemm_problem("f16", 65536, 1024, 4, 0, 0), oc.View(65536, 1024, 4, 1, 2, 4, 1)),
         (gs.gemm_problem("f16", 77, 53, 41, 0, 0, 1, "f16"), oc.View(77, 53, 41, 1, 2, 2, 1)),
+        # A stored [k][m]
+        (gs.gemm_problem("f16", 2048, 1024, 512, 1, 0), oc.View(2048, 1024, 512, 1, 2, 4, 1, asrc=1)),
+        (gs.gemm_problem("f32", 200, 136, 72, 1, 1), oc.View(200, 136, 72, 1, 4, 4, 0, asrc=1)),
     ]
 
 
@@ -344,7 +347,7 @@ def _usable(p, view, s):
     """What gensor_construct assumes of the operands: aligned and dense, so vector accesses work exactly when the
     contiguous extents are whole vectors; direct staging takes whole k tiles."""
     epc = 16 // view.e
-    vec_ok = view.bsrc == 2 or (view.K % epc == 0 and (view.bsrc == 0 or view.N % epc == 0))
+    vec_ok = view.bsrc == 2 or ((view.M if view.asrc else view.K) % epc == 0 and (view.K if view.bsrc == 0 else view.N) % epc == 0)
     if s.vec_bytes == 16 and not vec_ok:
         return False
     if s.direct_lds and view.bsrc != 2 and view.K % s.tile[2][0] != 0:
@@ -376,10 +379,11 @@ def test_pick_is_the_cheapest_instance_on_a_state_the_walks_kept():
     assert (hw.compute_units, hw.lds_bytes_per_cu, hw.regs_per_lane, hw.lds_banks, hw.lds_bank_bytes) == \
         (HW.compute_units, HW.lds_bytes_per_cu, HW.regs_per_lane, HW.lds_banks, HW.lds_bank_bytes)
     assert tuple(hw.latency_ns) == HW.latency_ns and tuple(hw.bandwidth_gbs) == HW.bandwidth_gbs
-    for p, view in _views():
+    variants = ((0, None, OPTS), (9, None, OPTS), (0, gs.ConstructOpts(0, 0, 0, 0, 0, 1), oc.Opts(no_vthread=1)))
+    for i, (p, view) in enumerate(_views()):
         insts = [s for s in _instances(gs, p) if _usable(p, view, s)]
         assert insts
-        for seed, co, oo in ((0, None, OPTS), (9, None, OPTS), (0, gs.ConstructOpts(0, 0, 0, 0, 0, 1), oc.Opts(no_vthread=1))):
+        for seed, co, oo in (variants if i < 3 else variants[:1]):        # (the oracle's 4096 walks take seconds per case)
             kept = oc.kept_states(view, HW, oo, seed)
             full = {k[0:1] + k[3:4] + k[6:7] + k[1:2] + k[4:5] + k[7:8] + k[9:11] for k in kept}     # bm bn bk wm wn kg vm vn
             spatial = {c[0:2] + c[3:5] for c in full}
@@ -468,5 +472,5 @@ def test_construct_rejects_bad_problems():
         gs.construct(gs.gemm_problem("f16", 0, 4, 4))
     assert e.value.status == 1
     with pytest.raises(gs.GensorError) as e:
-        gs.construct(gs.gemm_problem("f16", 64, 64, 64, 1, 0))
+        gs.construct(gs.gemm_problem("f16", 64, 64, 64, 0, 0, 1, "bf16"))      # output neither fp32 nor the input type
     assert e.value.status == 2

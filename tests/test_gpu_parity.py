@@ -26,9 +26,9 @@ def _round_up(x, m):
     return (x + m - 1) // m * m
 
 
-def run_gemm(gs, dtype, M, N, K, transB, sched, A, B, alpha=1.0, beta=0.0, C0=None, batch=1, out_dtype="f32"):
+def run_gemm(gs, dtype, M, N, K, transB, sched, A, B, alpha=1.0, beta=0.0, C0=None, batch=1, out_dtype="f32", transA=0):
     import torch
-    p = gs.gemm_problem(dtype, M, N, K, 0, transB, batch, out_dtype)
+    p = gs.gemm_problem(dtype, M, N, K, transA, transB, batch, out_dtype)
     dA, dB = gs.to_device(A, dtype), gs.to_device(B, dtype)
     shape = (batch, M, N) if batch > 1 else (M, N)
     if C0 is None:
@@ -51,7 +51,7 @@ def instance_cases(gs):
     for idx in range(gs.num_instances()):
         for dt in ("f32", "f16", "bf16"):
             for out_dt in sorted({"f32", dt}):
-                for tb, op in ((1, "gemm"), (0, "gemm"), (0, "conv"), (0, "conv1x1"), (0, "conv_pw2")):
+                for tb, op in ((1, "gemm"), (0, "gemm"), (1, "gemm_ta"), (0, "gemm_ta"), (0, "conv"), (0, "conv1x1"), (0, "conv_pw2")):
                     if op == "conv1x1" and out and out[-1][0] == idx:
                         continue                      # already covered with 3x3 filters
                     if op == "conv_pw2":              # pointwise, stride 2: the sampling B source
@@ -59,7 +59,7 @@ def instance_cases(gs):
                     elif op.startswith("conv"):
                         p = gs.conv_problem(dt, 1, 8, 8, 8, 8, 3 if op == "conv" else 1, 3 if op == "conv" else 1, 1, 1, out_dt)
                     else:
-                        p = gs.gemm_problem(dt, 64, 64, 64, 0, tb, 1, out_dt)
+                        p = gs.gemm_problem(dt, 64, 64, 64, 1 if op == "gemm_ta" else 0, tb, 1, out_dt)
                     s = gs.instance_schedule(idx, p)
                     if s is not None:
                         out.append((idx, dt, out_dt, op, tb, s))
@@ -76,14 +76,15 @@ def test_every_instance_bit_exact_on_integers(gs):
         vec = s.vec_bytes == 16
         print(f"instance {idx} {dt}->{out_dt} {op} transB={tb} tile {bm}x{bn}x{bk} vec={vec} direct={s.direct_lds}", flush=True)
         lim = 1 if out_dt == "bf16" else 4      # keep results exactly representable in the output type
-        if op == "gemm":
-            M = bm + 17
+        if op in ("gemm", "gemm_ta"):
+            ta = 1 if op == "gemm_ta" else 0
+            M = bm + (17 if not (ta and vec) else 16)          # an m-contiguous A read in vectors needs M in whole vectors
             N = bn + (8 if vec else 9)
             K = 2 * bk + (0 if s.direct_lds else (epc if vec else 5))
-            A = inputs.small_ints(100 + idx, (M, K), dt, -lim, lim)
+            A = inputs.small_ints(100 + idx, (K, M) if ta else (M, K), dt, -lim, lim)
             B = inputs.small_ints(200 + idx, (N, K) if tb else (K, N), dt, -lim, lim)
-            want = ops.gemm(A, B, dt, transB=tb)
-            got = run_gemm(gs, dt, M, N, K, tb, s, A, B, out_dtype=out_dt)
+            want = ops.gemm(A, B, dt, transA=ta, transB=tb)
+            got = run_gemm(gs, dt, M, N, K, tb, s, A, B, out_dtype=out_dt, transA=ta)
         else:
             import torch
             c, r = (8, 3) if vec else (5, 3)        # K = c*r*r: 72 (whole chunks) or 45
@@ -306,7 +307,7 @@ def test_error_paths_launch_nothing(gs):
     with pytest.raises(gs.GensorError) as e:
         gs.gemm(bad, A, A, Cc)
     assert e.value.status == 1
-    pt = gs.gemm_problem("f16", 64, 64, 64, 1, 1)     # transposed A has no kernel
+    pt = gs.gemm_problem("f16", 64, 64, 64, 0, 1, 1, "bf16")     # output neither fp32 nor the input type: no kernel
     with pytest.raises(gs.GensorError) as e:
         gs.gemm(pt, A, A, Cc)
     assert e.value.status == 2
@@ -861,3 +862,43 @@ def test_split_k_many_calls_on_one_workspace_stay_exact(gs, M, N, K, split):
         bad += (dC != want).sum()
     torch.cuda.synchronize()
     assert int(bad) == 0
+
+
+# ----------------------------------------------------------------------------------------------------------
+# transA: A stored [K][M]
+# ----------------------------------------------------------------------------------------------------------
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("transB", [0, 1])
+def test_gemm_with_a_stored_transposed(gs, dtype, transB):
+    """C = alpha A^T-stored x op(B) + beta C under the constructed schedule: real values at the stated tolerance,
+    integers exactly, aligned and unaligned extents, batched, and split along k."""
+    import torch
+    for (M, N, K, batch) in ((392, 264, 520, 1), (77, 53, 41, 1), (136, 200, 192, 3)):
+        shp = lambda r, c: (batch, r, c) if batch > 1 else (r, c)
+        A = inputs.uniform_pm1(41, shp(K, M), dtype)
+        B = inputs.uniform_pm1(42, shp(N, K) if transB else shp(K, N), dtype)
+        C0 = inputs.uniform_pm1(43, shp(M, N), "f32")
+        got = run_gemm(gs, dtype, M, N, K, transB, None, A, B, 1.5, -0.5, C0, batch=batch, transA=1)
+        ref = (lambda a, b, c: ops.gemm(a, b, dtype, transA=1, transB=transB, alpha=1.5, beta=-0.5, C0=c))
+        want = np.stack([ref(A[i], B[i], C0[i]) for i in range(batch)]) if batch > 1 else ref(A, B, C0)
+        err = ops.rel_frobenius(got, want)
+        print(dtype, "transB", transB, (M, N, K, batch), "rel frobenius", err, flush=True)
+        assert err <= TOL[dtype]
+        Ai = inputs.small_ints(44, shp(K, M), dtype, -3, 3)
+        Bi = inputs.small_ints(45, shp(N, K) if transB else shp(K, N), dtype, -3, 3)
+        goti = run_gemm(gs, dtype, M, N, K, transB, None, Ai, Bi, batch=batch, transA=1)
+        refi = lambda a, b: ops.gemm(a, b, dtype, transA=1, transB=transB)
+        wanti = np.stack([refi(Ai[i], Bi[i]) for i in range(batch)]) if batch > 1 else refi(Ai, Bi)
+        assert np.array_equal(goti, wanti)
+    # split along k: few tiles, deep reduction
+    M, N, K = 192, 136, 2048
+    p = gs.gemm_problem(dtype, M, N, K, 1, transB)
+    scheds = _split_schedules(gs, p, 4, {(128, 128), (64, 64)})
+    assert scheds
+    A = inputs.small_ints(46, (K, M), dtype, -2, 2)
+    B = inputs.small_ints(47, (N, K) if transB else (K, N), dtype, -2, 2)
+    want = ops.gemm(A, B, dtype, transA=1, transB=transB)
+    for s in scheds[:3]:
+        print("transA split-k instance", s.kernel_id, flush=True)
+        assert np.array_equal(_run_split(gs, p, s, dtype, A, B, gs.gemm_workspace(p, s)), want)
