@@ -123,7 +123,7 @@ class Hw:
 class Opts:
     T0: float = 2.0 ** 30
     threshold: float = 2.0 ** -70
-    chains: int = 4096
+    chains: int = 16384
     keep_policy: int = 0
     tiling_benefit: int = 0
     no_vthread: int = 0
