@@ -395,11 +395,11 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   if (t_lds > t_main) t_main = t_lds;
   if (t_feed > t_main) t_main = t_feed;
   // every k tile boundary (barrier, refill of the fragment pipeline) exposes a share of the memory latency
-  // (a ring of three and more stages keeps more tiles in flight; measured to pay for k-contiguous operands)
+  // (a ring of three and more stages keeps more tiles in flight)
   const double t_ktile = 0.3 * hw.latency_ns[0] * 1e-3;
   auto sync_time = [&](double tiles_k) {
     double t = tiles_k * t_ktile;
-    if (stages > 2 && v.bsrc == B_KC) t = t / (stages - 1);
+    if (stages > 2 && (v.bsrc == B_KC || v.bsrc == B_NC)) t = t / (stages - 1);
     if (stages == 1) t = t + (tiles_k - 1.0) * 4.0 * t_ktile;          // a single buffer: each further tile waits out its own fetch
     return t;
   };
@@ -415,7 +415,12 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   const double hide = resident < 2.0 ? resident : 2.0;
   // a part writes its partial tile, and one part in `split` reads the others' and stores C
   const double t_swap = bm * bn * 4.0 / (0.8 * hbm_bw_cu);
-  const double t_cu = cu_whole * (t_main + t_epi / hide) + cu_part * (t_part + t_swap + (t_swap * (split - 1) + t_epi) / split / hide) + t_fill;
+  // the exchange is a chain of memory round trips whatever the tile size: the slot stores written through and awaited,
+  // the arrival count, the other parts' slots fetched past the L2 (measured: a two-way split of the 128x128 tiles of
+  // 8192x768x3072 takes 9 us longer than its halved k loop explains)
+  const double t_chain = 10.0 * hw.latency_ns[0] * 1e-3;
+  const double t_cu = cu_whole * (t_main + t_epi / hide) +
+                      cu_part * (t_part + t_chain + t_swap + (t_swap * (split - 1) + t_epi) / split / hide) + t_fill;
   const double bytes_total = (double)v.batch * ((double)e * ((double)v.M * v.K + (double)v.K * v.N) + (double)eo * v.M * v.N);
   const double bytes_swap = split > 1 ? (tiles - whole) * (2.0 * split - 1.0) * bm * bn * 4.0 : 0.0;
   const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3) + bytes_swap / (0.25 * hw.bandwidth_gbs[0] * 1e3);

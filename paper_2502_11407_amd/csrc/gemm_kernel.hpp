@@ -560,6 +560,17 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
   constexpr bool DEEP = C::DIRECT && C::STAGES == 2 && C::KSTEPS == 4 && C::MBLK * C::NBLK >= 16;
   constexpr int FSETS = DEEP ? 4 : 2;
   u32x4 fa[FSETS][C::MBLK], fb[FSETS][C::NBLK];
+  // Direct staging with an n-contiguous 16-bit B: the transposing fragment reads are issued from inline assembly.
+  // A compiler-issued LDS read that it cannot tell apart from the destinations of the direct loads in flight is
+  // preceded by a wait for ALL of them (vmcnt(0)), which it does for the transposing-read builtin: every k tile
+  // then waited out the full latency of the loads just issued for the next one.  The assembly reads are invisible
+  // to the compiler's counter bookkeeping, so the kernel waits for them itself: `settle` below, in front of the
+  // MFMAs that consume a register set.  LDS operations complete in issue order and the statements are volatile,
+  // hence ordered: "at most N outstanding", with N no more than the number of such reads issued after the awaited
+  // ones, means the awaited ones have landed.  The halves stay separate values until that wait (a copy of a pending
+  // register would read stale data); the compiler's own waits only get more conservative by operations it does not see.
+  constexpr bool ASM_TR = C::NC_DIRECT && ES == 2;
+  u32x2 fbl[ASM_TR ? FSETS : 1][ASM_TR ? C::NBLK : 1], fbh[ASM_TR ? FSETS : 1][ASM_TR ? C::NBLK : 1];
   // Fragment of one MFMA block from a tile stored [k][rows] (an n-contiguous B or an m-contiguous A), `first` =
   // the block's first row/column inside the tile, `direct` = the tile is unpadded and XOR-swizzled.
   auto read_transposed = [&](GENSOR_LDS char* base, int pitch, int first, int ks, auto direct_tag, int v) -> u32x4 {
@@ -615,12 +626,47 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       if constexpr (C::BSRC == B_KC) {
         const int row = block_col(bj) + frow;
         fb[buf][bj] = *(GENSOR_LDS u32x4*)(bbase + row * C::PITCH_K + swizzled_chunk(row, ch, C::RPP, C::VN) * 16);
+      } else if constexpr (ASM_TR) {
+        const int g = lane >> 4, s = lane & 15;
+        int krow, col;
+        if constexpr (MB == 32) {
+          krow = ks * C::KG + (g >> 1) * 8 + (s >> 2);
+          col = block_col(bj) + (g & 1) * 16 + (s & 3) * 4;
+        } else {
+          krow = ks * C::KG + g * 8 + (s >> 2);
+          col = block_col(bj) + (s & 3) * 4;
+        }
+        const uint32_t a0 = (uint32_t)(uintptr_t)(bbase + krow * C::PITCH_N + ((col * 2) ^ nc_swizzle(krow, C::VN)));
+        const uint32_t a1 = (uint32_t)(uintptr_t)(bbase + (krow + 4) * C::PITCH_N + ((col * 2) ^ nc_swizzle(krow + 4, C::VN)));
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(fbl[buf][bj]) : "v"(a0));
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(fbh[buf][bj]) : "v"(a1));
       } else {
         fb[buf][bj] = read_transposed(bbase, C::PITCH_N, block_col(bj), ks, std::integral_constant<bool, C::NC_DIRECT>{}, C::VN);
       }
     }
   };
-  auto mma = [&](int buf) {
+  // groups: how many later read_frags calls (each 2 * NBLK transposing reads) have been issued since the one that
+  // filled register set buf -- a lower bound; 0 waits for every LDS operation
+  auto settle = [&](int buf, auto groups_tag) {
+    if constexpr (ASM_TR) {
+      constexpr int N = decltype(groups_tag)::value * 2 * C::NBLK > 15 ? 15 : decltype(groups_tag)::value * 2 * C::NBLK;
+#pragma unroll
+      for (int bj = 0; bj < C::NBLK; ++bj) {
+        if (bj == 0) asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(fbl[buf][bj]), "+v"(fbh[buf][bj]) : "n"(N));
+        else asm volatile("" : "+v"(fbl[buf][bj]), "+v"(fbh[buf][bj]));
+        const u32x4 v = {fbl[buf][bj][0], fbl[buf][bj][1], fbh[buf][bj][0], fbh[buf][bj][1]};
+        fb[buf][bj] = v;
+      }
+    }
+  };
+  // Workgroup barrier of the k loop.  The transposing reads issued from assembly must have left the LDS before
+  // another wave may overwrite the stage they read; the compiler does not know of them, so the wait is explicit.
+  auto block_sync = [&]() {
+    if constexpr (ASM_TR) __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0); the other counters untouched
+    __syncthreads();
+  };
+  auto mma = [&](int buf, auto groups_tag) {
+    settle(buf, groups_tag);
 #pragma unroll
     for (int bi = 0; bi < C::MBLK; ++bi)
 #pragma unroll
@@ -687,21 +733,21 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       constexpr bool has_next = decltype(next_tag)::value, has_fetch = decltype(fetch_tag)::value;
       const int cur = kt & 1, nxt = cur ^ 1;
       read_frags(cur, 2, 2);
-      mma(0);
+      mma(0, std::integral_constant<int, 2>{});
       interleave();
       read_frags(cur, 3, 3);
-      mma(1);
+      mma(1, std::integral_constant<int, 2>{});
       interleave();
       if constexpr (has_next) {
         wait_deposits();
-        __syncthreads();
+        block_sync();
         read_frags(nxt, 0, 0);
         if constexpr (has_fetch) {
           fetch_a((kt + 2) * BK, cur, 0, 2);
           fetch_b((kt + 2) * BK, cur, 0, 2);
         }
       }
-      mma(2);
+      mma(2, std::integral_constant<int, has_next ? 2 : 1>{});
       if constexpr (has_fetch) interleave_vmem(std::true_type{});
       else interleave();
       if constexpr (has_next) {
@@ -711,7 +757,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
           fetch_b((kt + 2) * BK, cur, 1, 2);
         }
       }
-      mma(3);
+      mma(3, std::integral_constant<int, has_next ? 2 : 0>{});
       if constexpr (has_fetch) interleave_vmem(std::true_type{});
       else interleave();
     };
@@ -758,7 +804,8 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
           ring_barrier();
           read_frags(nxt, 0, 0);
         }
-        mma(ks & 1);
+        if (ks + 1 < C::KSTEPS || more) mma(ks & 1, std::integral_constant<int, 1>{});
+        else mma(ks & 1, std::integral_constant<int, 0>{});
         interleave();
       }
       return nxt;
@@ -804,10 +851,11 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
         } else if constexpr (more) {
           commit(nxt);
           wait_deposits();
-          __syncthreads();
+          block_sync();
           read_frags(nxt, 0, 0);
         }
-        mma(ks & 1);
+        if (ks + 1 < C::KSTEPS || more) mma(ks & 1, std::integral_constant<int, 1>{});
+        else mma(ks & 1, std::integral_constant<int, 0>{});
         if (FS > 1 && more && ks < FS) interleave_vmem(std::false_type{});
         else interleave();
       }
@@ -828,10 +876,10 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
 #pragma unroll
       for (int ks = 0; ks < C::KSTEPS; ++ks) {
         read_frags(cur, ks, 0);
-        mma(0);
+        mma(0, std::integral_constant<int, 0>{});
       }
       if constexpr (C::STAGES == 1) {
-        __syncthreads();                       // everyone is done reading the single buffer
+        block_sync();                       // everyone is done reading the single buffer
         if constexpr (C::DIRECT) {
           if (more) {
             fetch_a((kt + 1) * BK, 0);
@@ -841,7 +889,7 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
       }
       if (more) commit(nxt);
       wait_deposits();
-      __syncthreads();
+      block_sync();
     }
   }
 

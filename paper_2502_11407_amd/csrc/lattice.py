@@ -182,6 +182,10 @@ def lattice():
             out.append(_inst("f32", "f32", bm, bn, 32, wm, wn, mb, bsrc=bsrc, asrc="MC"))
         out.append(_inst("f32", "f32", 64, 64, 32, 32, 32, 32, 1, 1, bsrc=bsrc, asrc="MC"))
         out.append(_inst("f32", "f32", 64, 64, 16, 32, 32, 16, bsrc=bsrc, vec=0, asrc="MC"))
+    # three-stage rings for an n-contiguous B (the mid-size eight-wave tiles), like the k-contiguous ones above
+    for dt in ("f16", "bf16"):
+        for (bm, bn) in ((128, 256), (256, 128)):
+            out.append(_inst(dt, "f32", bm, bn, 64, 64, 64, 32, bsrc="NC", stages=3, direct=1))
     for i, d in enumerate(out):
         d["id"] = i
     keys = [(d["dt"], d["out"], d["bm"], d["bn"], d["bk"], d["wm"], d["wn"], d["mb"], d["vm"], d["vn"], d["bsrc"], d["vec"],
