@@ -389,7 +389,8 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   double par = resident * nwaves / hw.simds_per_cu;
   if (par > 4.0) par = 4.0;
   double overlap = 0.8 + 0.15 * par;
-  if (direct && v.bsrc == B_KC) overlap += 0.05;      // measured: direct staging pays for k-contiguous operands only
+  if (direct && v.bsrc == B_KC) overlap += 0.05;      // measured: what direct staging pays for k-contiguous operands
+  if (direct && v.bsrc == B_NC) overlap += 0.03;      // ... and for an n-contiguous B
   if (direct && v.bsrc == B_KC && stages == 2 && wm * wn >= 128 * 128 && bk == 4 * kg) overlap += 0.16;   // the two-steps-ahead schedule of the one-wave-per-SIMD tiles (k-contiguous operands: measured)
   double t_main = t_mfma;
   if (t_lds > t_main) t_main = t_lds;
