@@ -1,9 +1,9 @@
-"""The kernels that issue their transposing LDS fragment reads from inline assembly (direct staging with an
-n-contiguous 16-bit B operand) wait for those reads themselves, because the compiler's counter bookkeeping does not
-see them.  This test compiles every such instance to assembly (this repository's own kernels, device code only, no
-GPU needed) and checks the contract instruction by instruction: a register written by `ds_read_b64_tr_b16` is not
-touched by any instruction until an `s_waitcnt lgkmcnt(k)` has executed with k no larger than the number of LDS
-operations issued after that read (LDS operations complete in issue order), along every path through the kernel."""
+"""The kernels that issue their LDS fragment reads from inline assembly (direct staging with an n-contiguous 16-bit
+B operand) wait for those reads themselves, because the compiler's counter bookkeeping does not see them.  This test
+compiles every such instance to assembly (this repository's own kernels, device code only, no GPU needed) and checks
+the contract instruction by instruction: a register written by an LDS read is not touched by any instruction until
+an `s_waitcnt lgkmcnt(k)` has executed with k no larger than the number of LDS operations issued after that read
+(LDS operations complete in issue order), along every path through the kernel."""
 import os
 import re
 import subprocess
@@ -73,7 +73,7 @@ def check_function(lines):
                         del pending[r]
                 if op.startswith("ds_"):
                     pending = {r: age + 1 for r, age in pending.items()}
-                    if op == "ds_read_b64_tr_b16":
+                    if op.startswith("ds_read"):
                         if i not in seen_reads:
                             seen_reads.add(i)
                             reads += 1
@@ -111,8 +111,10 @@ def _functions(asm):
 
 
 def test_checker_catches_an_early_use():
-    good = ["ds_read_b64_tr_b16 v[4:5], v9", "ds_read_b128 v[10:13], v9", "s_waitcnt lgkmcnt(1)", "v_mov_b32_e32 v0, v4", "s_endpgm"]
-    assert check_function(good) == ([], 1)
+    good = ["ds_read_b64_tr_b16 v[4:5], v9", "ds_read_b128 v[10:13], v9", "s_waitcnt lgkmcnt(1)", "v_mov_b32_e32 v0, v4",
+            "s_waitcnt lgkmcnt(0)", "v_mov_b32_e32 v1, v10", "s_endpgm"]
+    assert check_function(good) == ([], 2)
+    assert check_function(good[:4] + ["v_mov_b32_e32 v1, v10", "s_endpgm"])[0]          # the second read is still pending
     early = ["ds_read_b64_tr_b16 v[4:5], v9", "v_mov_b32_e32 v0, v4", "s_endpgm"]
     assert check_function(early)[0]
     weak = ["ds_read_b64_tr_b16 v[4:5], v9", "s_waitcnt lgkmcnt(1)", "v_mfma_f32_32x32x16_f16 v[16:31], v[0:3], v[4:7], v[16:31]", "s_endpgm"]
@@ -152,5 +154,5 @@ def test_every_instance_with_assembly_reads_waits_for_them(tmp_path):
     for idx, res in results:
         assert res, idx
         for violations, reads in res:
-            assert reads > 0, "instance %d: no transposing reads found" % idx
+            assert reads > 0, "instance %d: no LDS reads found" % idx
             assert not violations, "instance %d: %s" % (idx, violations[:3])
