@@ -293,7 +293,8 @@ double predict_patch(const GemmView& v, const gensor_hw& hw, int bm, int bn, int
   const int epc = 16 / e;
   const int64_t RS = v.cr * v.cs;
   const double nst = std::ceil((double)v.cc / bk);
-  double out_rows = std::ceil((double)(bn - 1) / (double)v.Q) + 1.0;
+  const int64_t px = conv_tile_px(bn, v.N, v.Q, (v.M + bm - 1) / bm, hw.compute_units);   // the kernel's own rule
+  double out_rows = px % v.Q == 0 ? (double)(px / v.Q) : std::ceil((double)(px - 1) / (double)v.Q) + 1.0;
   if (out_rows > (double)(v.cn * v.P)) out_rows = (double)(v.cn * v.P);
   const int64_t rows = ((int64_t)out_rows - 1) * v.cstride + v.cr + 2 * v.cpad;
   const int64_t pw = v.cw + 2 * v.cpad;
@@ -311,11 +312,13 @@ double predict_patch(const GemmView& v, const gensor_hw& hw, int bm, int bn, int
   if (by_regs < occ) occ = by_regs;
   if (occ > 8) occ = 8;
   if (occ < 1) return -1.0;
-  const double tiles = std::ceil((double)v.M / bm) * std::ceil((double)v.N / bn);
+  const double tiles = std::ceil((double)v.M / bm) * std::ceil((double)v.N / (double)px);
   const double cu_tiles = std::ceil(tiles / hw.compute_units);
   const double resident = (double)occ < cu_tiles ? (double)occ : cu_tiles;
+  // the busiest CU runs whole groups of resident workgroups one after the other; the others even it out in part
   double rounds = tiles / (double)(hw.compute_units * occ);
   if (rounds < 1.0) rounds = 1.0;
+  rounds = 0.7 * std::ceil(cu_tiles / (double)occ) + 0.3 * rounds;
   double share = resident * nwaves / hw.simds_per_cu;
   if (share < 1.0) share = 1.0;
   const double peak_simd = (e == 2 ? hw.mfma_tflops_16bit : hw.mfma_tflops_f32) * 1e6 / (double)(hw.compute_units * hw.simds_per_cu);
@@ -325,10 +328,10 @@ double predict_patch(const GemmView& v, const gensor_hw& hw, int bm, int bn, int
   const double t_lds = (double)(RS * ksteps * ((wm / mb) + (wn / mb))) * 1024.0 * nwaves / lds_bw * resident;
   const double l2_bw = hw.l2_bandwidth_gbs * 1e3 / hw.compute_units;
   const double t_feed = (double)(rows * v.cw * bk * e + bm * RS * bk * e) / (0.5 * l2_bw);     // 16-byte gathers: half the L2 rate; hidden by the other resident workgroups
-  const double t_fixed = (0.75 * hw.latency_ns[0] + 1.5 * hw.latency_ns[1]) * 1e-3;
+  const double t_fixed = 0.25 * hw.latency_ns[0] * 1e-3;
   const double t_stage = t_mfma + t_lds + t_feed + t_fixed;
-  const double t_pro = (2.0 * hw.latency_ns[0] + 6.0 * hw.latency_ns[1]) * 1e-3;
-  const double t_epi = (double)(bm * bn * eo) / (0.6 * hw.bandwidth_gbs[0] * 1e3 / hw.compute_units);
+  const double t_pro = 0.625 * hw.latency_ns[0] * 1e-3;
+  const double t_epi = (double)(bm * px * eo) / (1.5 * hw.bandwidth_gbs[0] * 1e3 / hw.compute_units);
   const double t_cu = rounds * (t_pro + nst * t_stage + t_epi);
   const double bytes_total = (double)(e * (v.cn * v.cc * v.ch * v.cw + v.M * v.K) + eo * v.M * v.N);
   const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3);

@@ -17,6 +17,10 @@
 //     never written and stay zero.  Global reads run along x (16 bytes per channel), an
 //     8x8 (4x4 for fp32) register transpose turns them into channel-contiguous 16-byte
 //     LDS writes, so every input element is fetched once per workgroup, not once per tap.
+// A workgroup's pixels are BN consecutive (image, row, col) positions, or, when an output row is shorter
+// than BN, a whole number of output rows (KernelArgs::cTilePx, chosen by the host): the patch then has
+// no partial rows and the tile count can be matched to the compute units; waves whose columns lie
+// beyond the tile's pixels only help with the staging.
 // A lane's B fragment for tap (r, s) and channel chunk c is then ONE aligned 16-byte LDS
 // read at  lane_base + (r*PW + s)*SLOT + c*16 : the tap is a scalar offset, there is no
 // per-tap address arithmetic and no im2col buffer.
@@ -117,7 +121,8 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
     tile_m = pi * panel + r % rows_here;
     tile_n = r / rows_here;
   }
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int m0 = tile_m * BM, n0 = tile_n * args.cTilePx;
+  const int n_end = min(args.N, n0 + args.cTilePx);        // columns of the tile at or beyond it belong to the next workgroup
 
   // geometry
   const int Cc = args.cC, H = args.cH, W = args.cW, R = args.cR, S = args.cS, P = args.cP, Q = args.cQ;
@@ -177,6 +182,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
     if (fmode == 2) {
 #pragma unroll
       for (int u = 0; u < C::U9_MAX; ++u) {
+        if ((C::THREADS - 64 - wave * 64) + u * C::THREADS >= a_units) continue;      // no lane of this wave holds a unit
         const int oct = ((C::THREADS - 1 - tid) + u * C::THREADS) % C::OCT;
         const bool ok = a_goff[u] >= 0 && c0 + oct * EPC < Cc;
 #pragma unroll
@@ -186,6 +192,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
     } else {
 #pragma unroll
       for (int v = 0; v < C::A_VEC_MAX; ++v) {
+        if (wave * 64 + v * C::THREADS >= a_vecs) continue;                            // no lane of this wave holds a piece
         // a piece starts at channel c0 + (t*EPC)/RS of the run; pieces are wholly inside or wholly
         // beyond the channels that exist (C and the channel tile are multiples of EPC)
         const int t = (tid + v * C::THREADS) % a_vec_per_row;
@@ -291,6 +298,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
   auto fetch_patch = [&](int c0) {
 #pragma unroll
     for (int u = 0; u < C::UNITS_MAX; ++u) {
+      if (wave * 64 + u * C::THREADS >= units) continue;                               // no lane of this wave holds a unit
       // a channel group at or beyond C reads as zero (C is a multiple of the group size)
       const int oct = (tid + u * C::THREADS) % C::OCT;
       const bool ok = u_goff[u] >= 0 && c0 + oct * EPC < Cc;
@@ -346,7 +354,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
 #pragma unroll
   for (int bj = 0; bj < C::NBLK; ++bj) {
     int n = n0 + block_col(bj) + frow;
-    n = n < args.N ? n : args.N - 1;
+    n = n < n_end ? n : n_end - 1;
     const int g = n / Q, q = n - g * Q;
     const int img = g / P, p = g - img * P;
     b_base[bj] = ((img * Hp + p * stride - R0) * PW + q * stride) * SLOT;
@@ -379,6 +387,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
 #pragma unroll
           for (int bj = 0; bj < C::NBLK; ++bj) MF::run(af[buf][ks][bi], bf[buf][ks][bj], acc[bi][bj]);
     };
+    if (n0 + wave_n * C::WN >= n_end) return;            // a wave whose columns all lie beyond the tile's pixels
     int r = 0, s2 = 0;                                  // the next tap to read
     auto advance = [&]() { if (++s2 == S) { s2 = 0; ++r; } };
     read_tap(0, 0, 0);
@@ -456,7 +465,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
   // are a large share of the launch (64 channels x 3x3, 64 filters: 17.9 -> 15.6 us), write-back for a deep
   // one, where the L2 drains them under the next tile's work (reductions of 1152 and 2304: write-through
   // measured 1.5-2.5 % slower).
-  {
+  if (n0 + wave_n * C::WN < n_end) {
     constexpr int POLICY = THROUGH ? 16 : 0;
 #pragma unroll
     for (int bj = 0; bj < C::NBLK; ++bj) {
@@ -469,7 +478,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
         for (int v = 0; v < MF::NACC; ++v) {
           const int rr = (MB == 32) ? 8 * (v / 4) + 4 * fgrp + (v % 4) : 4 * fgrp + v;
           const int row = m0 + block_row(bi) + rr;
-          const uint32_t off = (row < args.M && col < args.N) ? (uint32_t)((cbase + row * PQ) * OS) : OOB;
+          const uint32_t off = (row < args.M && col < n_end) ? (uint32_t)((cbase + row * PQ) * OS) : OOB;
           const float val = acc[bi][bj][v];
           if constexpr (OS == 4) {
             __builtin_amdgcn_raw_buffer_store_b32(as_u32(val), rs_out, off, 0, POLICY);

@@ -67,6 +67,7 @@ struct KernelArgs {
   int32_t cC, cH, cW, cR, cS, cP, cQ, cStride, cPad;
   // patch-staged convolution only: images, LDS plan and tensor sizes in bytes (each < 2^31)
   int32_t cN, cApitch, cPatchRows, cStageBytes;
+  int32_t cTilePx;                 // output pixels per workgroup (at most BN; whole output rows when they are shorter than BN)
   int64_t cInBytes, cWBytes, cOutBytes;
 };
 

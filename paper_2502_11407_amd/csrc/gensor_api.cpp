@@ -92,7 +92,7 @@ void schedule_from_instance(const InstanceDesc& d, gensor_schedule* s) {
   s->wg_remap = 4;
 }
 
-bool conv_patch_plan(const InstanceDesc& d, const GemmView& v, ConvPlan* plan) {
+bool conv_patch_plan(const InstanceDesc& d, const GemmView& v, ConvPlan* plan, int round_units) {
   const int64_t lim = 0x7fffffffll;
   const int epc = 16 / v.esize;
   const int64_t rs = v.cr * v.cs;
@@ -109,9 +109,12 @@ bool conv_patch_plan(const InstanceDesc& d, const GemmView& v, ConvPlan* plan) {
   if ((int64_t)d.bm * pl.a_pitch >= (1 << 20)) return false;
   // patch rows: the most stacked padded input rows any pixel tile touches
   const int64_t hp = v.ch + 2 * v.cpad, pw = v.cw + 2 * v.cpad;
+  const int64_t cus = round_units > 0 ? round_units : gensor_hw_mi355x()->compute_units;
+  const int64_t px = conv_tile_px(d.bn, v.N, v.Q, (v.M + d.bm - 1) / d.bm, cus);
+  pl.tile_px = (int)px;
   int64_t rows = 0;
-  for (int64_t n0 = 0; n0 < v.N; n0 += d.bn) {
-    const int64_t n1 = (n0 + d.bn < v.N ? n0 + d.bn : v.N) - 1;
+  for (int64_t n0 = 0; n0 < v.N; n0 += px) {
+    const int64_t n1 = (n0 + px < v.N ? n0 + px : v.N) - 1;
     const int64_t g0 = n0 / v.Q, g1 = n1 / v.Q;
     const int64_t r0 = (g0 / v.P) * hp + (g0 % v.P) * v.cstride;
     const int64_t r1 = (g1 / v.P) * hp + (g1 % v.P) * v.cstride + v.cr - 1;
@@ -320,7 +323,10 @@ gensor_status run(const gensor_schedule* s, const gensor_problem* p, const GemmV
   }
   if (d->units) {
     ConvPlan pl;
-    if (!conv_patch_plan(*d, v, &pl)) return GENSOR_ERR_NO_SCHEDULE;
+    if (!conv_patch_plan(*d, v, &pl, s->round_units)) return GENSOR_ERR_NO_SCHEDULE;
+    a.cTilePx = pl.tile_px;
+    a.tiles_n = (int32_t)((v.N + pl.tile_px - 1) / pl.tile_px);
+    if ((int64_t)a.tiles_m * a.tiles_n > INT32_MAX) return GENSOR_ERR_UNSUPPORTED;
     a.cN = (int32_t)p->n; a.cApitch = pl.a_pitch; a.cPatchRows = pl.patch_rows; a.cStageBytes = pl.stage_bytes;
     a.cInBytes = pl.in_bytes; a.cWBytes = pl.w_bytes; a.cOutBytes = pl.out_bytes;
     a.batch = 1;

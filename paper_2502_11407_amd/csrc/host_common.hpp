@@ -21,11 +21,28 @@ struct GemmView {
 
 // LDS plan of a patch-staged convolution instance for one problem.
 struct ConvPlan {
-  int a_pitch, patch_rows, stage_bytes;
+  int a_pitch, patch_rows, stage_bytes, tile_px;
   int64_t in_bytes, w_bytes, out_bytes;
 };
-// False if instance d (a patch-staged convolution) cannot run the convolution in v.
-bool conv_patch_plan(const InstanceDesc& d, const GemmView& v, ConvPlan* plan);
+// Output pixels per workgroup of a patch-staged instance with a pixel tile of bn.  When output rows are
+// shorter than the tile, a workgroup takes a whole number of them (its patch then has no partial rows):
+// as many as fit, or fewer when that deals the tiles more evenly over `cus` compute units.  A tile's
+// time is taken as 0.55 of a full tile's (MFMA work, filters, set-up: they do not shrink with the pixels)
+// plus 0.45 in proportion to its pixels (patch loads, stores).
+inline int64_t conv_tile_px(int64_t bn, int64_t N, int64_t Q, int64_t tiles_m, int64_t cus) {
+  if (Q > bn) return bn;
+  auto cost = [&](int64_t px) {
+    const int64_t tiles = (N + px - 1) / px * tiles_m;
+    return (double)((tiles + cus - 1) / cus) * (0.55 * (double)bn + 0.45 * (double)px);
+  };
+  int64_t best = bn / Q * Q;
+  for (int64_t r = bn / Q - 1; r >= 1; --r)
+    if (cost(r * Q) < cost(best)) best = r * Q;
+  return best;
+}
+// False if instance d (a patch-staged convolution) cannot run the convolution in v.  round_units: the
+// compute units the tiles are dealt over (0: the MI355X's).
+bool conv_patch_plan(const InstanceDesc& d, const GemmView& v, ConvPlan* plan, int round_units = 0);
 
 // A pointwise convolution (1x1 filter, no padding) is O[img] = W[k][c] * X[img][c][P*Q] with
 // X the input sampled at the stride: a batched GEMM over the images with an n-contiguous B.
