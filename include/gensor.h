@@ -123,7 +123,7 @@ const gensor_hw* gensor_hw_mi355x(void);
 typedef struct {
   double T0;                  /* initial (and per-level restart) temperature, default 2^30 */
   double threshold;           /* stop when T <= threshold, default 2^-70 (100 steps, Section IV-D) */
-  int32_t chains;             /* independent seeded walks, default 16384 (about 60 ms of construction) */
+  int32_t chains;             /* independent seeded walks, default 16384 (about 30 ms of construction) */
   int32_t keep_policy;        /* 0: keep every complete state; 1: the paper's printed keep probability */
   int32_t tiling_benefit;     /* 0: Eq. 1 as printed; 1: footprint ratio inverted (ablation) */
   int32_t no_vthread;         /* 1: setVThread disabled (ablation) */
