@@ -490,7 +490,8 @@ def main():
         for item in args.launch_only.split(","):
             name, _, variant = item.partition(":")
             wl = (inputs.unbalanced_gemm(int(name[1:])) if name[0] == "u" else
-                  inputs.deep_k_gemm(int(name[1:])) if name[0] == "d" else inputs.all_configs()[name])
+                  inputs.deep_k_gemm(int(name[1:])) if name[0] == "d" else
+                  inputs.paper_conv(int(name[1:]) - 1) if name[0] == "C" else inputs.all_configs()[name])
             c = Case(gs, inputs, wl, gs.ConstructOpts(0, 0, 0, 0, 0, 1) if variant == "no_vthread" else None)
             for _ in range(20):
                 c.launch()

@@ -201,6 +201,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
       }
     }
   };
+  fetch_a(0);                      // the first stage's loads go out before the rest of the set-up
   // fmode 2: element (channel c, tap rs) of a unit is element c*9 + rs of its 9 pieces
   auto commit_a9 = [&](int st) {
     GENSOR_LDS char* base = lds + st * stage_bytes;
@@ -323,6 +324,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
       }
     }
   };
+  fetch_patch(0);
   auto commit_patch = [&](int st) {
     GENSOR_LDS char* base = lds + st * stage_bytes + a_bytes;
 #pragma unroll
@@ -412,8 +414,6 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
   };
 
   const int nstages = (Cc + BKC - 1) / BKC;
-  fetch_a(0);
-  fetch_patch(0);
   // ---- zero the patch buffers once (under the first loads): cells outside the images are
   // never written again
   {

@@ -40,7 +40,7 @@ def test_constructor_api_and_oracle_under_asan_ubsan(tmp_path):
     assert r.returncode == 0, r.stderr[-3000:]
     objs.append(obj)
     exe = str(tmp_path / "host_check")
-    r = subprocess.run([HIPCC, "-fsanitize=address", "-fsanitize=undefined"] + objs + ["-lm", "-o", exe], capture_output=True, text=True)
+    r = subprocess.run([HIPCC, "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined"] + objs + ["-lm", "-o", exe], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-3000:]
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
     r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=600)
