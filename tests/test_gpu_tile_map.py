@@ -54,27 +54,47 @@ def test_gemm_tile_map_every_element(gs, name):
         assert np.array_equal(got, want), f"{name} {tm}x{tn}x{batch}: {np.count_nonzero(got != want)} elements differ"
 
 
-@pytest.mark.parametrize("tiles_m,pixel_tiles,ragged", [(4, 67, True), (4, 64, False)])
-def test_conv_patch_tile_map_every_element(gs, tiles_m, pixel_tiles, ragged):
-    """The patch-staged convolution instance of the 3x3 benchmark shape over 268 tiles (not a multiple of 8) and 256."""
+def _conv_tile_px(bn, N, Q, tiles_m, cus=256):
+    """The library's rule for the pixels of a patch-staged workgroup (whole output rows when rows are shorter than
+    the tile, as many as fit or fewer when that deals the tiles more evenly), restated here only to choose
+    geometries with the wanted tile counts; the comparison below does not depend on it."""
+    import math
+    if Q > bn:
+        return bn
+    cost = lambda px: math.ceil(math.ceil(N / px) * tiles_m / cus) * (0.55 * bn + 0.45 * px)
+    best = bn // Q * Q
+    for r in range(bn // Q - 1, 0, -1):
+        if cost(r * Q) < cost(best):
+            best = r * Q
+    return best
+
+
+@pytest.mark.parametrize("tiles_m,whole_octets,ragged", [(4, False, True), (4, True, False)])
+def test_conv_patch_tile_map_every_element(gs, tiles_m, whole_octets, ragged):
+    """The patch-staged convolution instance of the 3x3 benchmark shape over a few hundred tiles, every output element
+    compared: once with a tile count that is a multiple of 8 (the XCD-contiguous remap) and once with one that is
+    not, the latter with a ragged last pixel tile and ragged filter rows."""
     import torch
     wl, s0 = _pick(gs, "cfg5_3x3")
     assert s0.direct_lds == 1
     bm, bn = s0.tile[0][0], s0.tile[1][0]
     k = tiles_m * bm - (5 if ragged else 0)
-    c, h = 32, 34
-    # n * P * Q output pixels = pixel_tiles * bn (less a ragged tail): P = h, Q = w with pad 1
-    pixels = pixel_tiles * bn - (40 if ragged else 0)
-    w = 32
-    n = -(-pixels // (h * w))
-    while n * h * w > pixel_tiles * bn or n * h * w <= (pixel_tiles - 1) * bn:
-        w += 1
-        n = max(1, round(pixels / (h * w)))
-        assert w < 200
+    c = 32
+    found = None
+    for h in range(30, 40):
+        for w in range(30, 44):
+            for n in range(10, 18):
+                N = n * h * w
+                px = _conv_tile_px(bn, N, w, tiles_m)
+                total = -(-N // px) * tiles_m
+                if total >= 256 and (total % 8 == 0) == whole_octets and (N % px != 0) == ragged:
+                    found = found or (n, h, w, px, total)
+    assert found, "no geometry with the wanted tile count"
+    n, h, w, px, total = found
     p = gs.conv_problem(wl.dtype, n, c, h, w, k, 3, 3, 1, 1)
     s = gs.instance_schedule(s0.kernel_id, p)
     assert s is not None
-    print(f"conv patch instance {s.kernel_id} tile {bm}x{bn}: {tiles_m} x {-(-n * h * w // bn)} tiles, n={n} c={c} h={h} w={w} k={k}", flush=True)
+    print(f"conv patch instance {s.kernel_id} tile {bm}x{bn}: {total} tiles of {px} pixels, n={n} c={c} h={h} w={w} k={k}", flush=True)
     I = inputs.small_ints(700, (n, c, h, w), wl.dtype, -2, 2)
     W = inputs.small_ints(701, (k, c, 3, 3), wl.dtype, -2, 2)
     dO = gs.empty_device((n, k, h, w)).fill_(float("nan"))
