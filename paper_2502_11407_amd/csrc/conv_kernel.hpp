@@ -276,7 +276,11 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
     else if (fmode == 1) commit_a1(st);
   };
 
-  // ---- patch staging plan.  A unit is EPC channels x EPC consecutive x of one patch row.
+  // ---- patch staging plan.  A unit is EPC channels x EPC consecutive x of one patch row.  Units are dealt
+  // channel group first, then patch row, then x segment: the 16 lanes of a 16-byte LDS write then differ in
+  // channel group (16 bytes) and row (the row pitch, an odd multiple of 32 bytes modulo 256 for the usual
+  // widths) and fall into different banks, where lanes that differ in x segment (8 pixels = 384 bytes) share
+  // them four ways (measured: 2-4 % on the 3x3 layers).
   const int w_segs = (W + EPC - 1) / EPC;
   const int units = patch_rows * w_segs * C::OCT;
   int u_goff[C::UNITS_MAX];        // element offset of (img, channel group, y, x segment) at channel tile 0, or -1
@@ -287,7 +291,7 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
   for (int u = 0; u < C::UNITS_MAX; ++u) {
     const int q = tid + u * C::THREADS;
     const int oct = q % C::OCT, t = q / C::OCT;
-    const int seg = t % w_segs, j = t / w_segs;
+    const int j = t % patch_rows, seg = t / patch_rows;
     const int srow = R0 + j;                       // stacked padded row
     const int img = srow / Hp, y = srow - img * Hp - pad;
     const bool ok = q < units && img < NI && y >= 0 && y < H;
