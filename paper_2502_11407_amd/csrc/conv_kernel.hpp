@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void subsample_input(const void* in, void* out
 // FMODE, how the filters are reordered on the way into the tile, is a template parameter: with all
 // three routes in one kernel the register allocation is the union of theirs (250 VGPRs, spills to
 // scratch) and every convolution shape measured ran 14 % slower.
-template <typename C, int FMODE, bool THROUGH>
+template <typename C, int FMODE, bool THROUGH, bool TAIL>
 __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs args) {
   typedef typename C::T T;
   typedef Mfma<T, C::MB> MF;
@@ -185,9 +185,10 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
         if ((C::THREADS - 64 - wave * 64) + u * C::THREADS >= a_units) continue;      // no lane of this wave holds a unit
         const int oct = ((C::THREADS - 1 - tid) + u * C::THREADS) % C::OCT;
         const bool ok = a_goff[u] >= 0 && c0 + oct * EPC < Cc;
+        // one select per unit: an offset at or above OOB stays out of range when the piece offsets are added
+        const uint32_t first = ok ? (uint32_t)((a_goff[u] + c0 * 9) * ES) : OOB;
 #pragma unroll
-        for (int i = 0; i < 9; ++i)
-          a_reg[u * 9 + i] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, ok ? (uint32_t)((a_goff[u] + c0 * 9 + i * EPC) * ES) : OOB, 0, 0);
+        for (int i = 0; i < 9; ++i) a_reg[u * 9 + i] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, first + (uint32_t)(i * 16), 0, 0);
       }
     } else {
 #pragma unroll
@@ -299,7 +300,10 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
     u_dst[u] = (j * PW + pad + seg * EPC) * SLOT + oct * 16;
     u_nx[u] = min(EPC, W - seg * EPC);
   }
-  const bool tail_check = (W % EPC) != 0;          // only then can a vector run past the end of the tensor
+  // TAIL: a vector can run past the end of the tensor when rows are not whole vectors.  The buffer's range check
+  // works dword by dword and returns the part inside, unless the vector starts off a dword boundary (16-bit
+  // elements and an odd row length): only then is the kernel instantiated with the element-wise fetch of the
+  // tensor's last vector (the launch decides), and every other shape runs loads without a test in front of each.
   auto fetch_patch = [&](int c0) {
 #pragma unroll
     for (int u = 0; u < C::UNITS_MAX; ++u) {
@@ -307,10 +311,11 @@ __global__ __launch_bounds__(C::THREADS) void conv_patch_kernel(const KernelArgs
       // a channel group at or beyond C reads as zero (C is a multiple of the group size)
       const int oct = (tid + u * C::THREADS) % C::OCT;
       const bool ok = u_goff[u] >= 0 && c0 + oct * EPC < Cc;
+      const uint32_t first = ok ? (uint32_t)((u_goff[u] + c0 * HW) * ES) : OOB;      // as for the filters: one select per unit
 #pragma unroll
       for (int i = 0; i < EPC; ++i) {
-        const uint32_t off = ok ? (uint32_t)((u_goff[u] + (c0 + i) * HW) * ES) : OOB;
-        if (tail_check && ok && off + 16u > (uint32_t)args.cInBytes) {
+        const uint32_t off = first + (uint32_t)(i * HW * ES);
+        if (TAIL && ok && off + 16u > (uint32_t)args.cInBytes) {
           // the very last vector of the tensor: a 16-byte read would leave the buffer, which
           // drops the valid part when the start is not dword aligned; fetch element-wise
           u32x4 v = {0u, 0u, 0u, 0u};

@@ -56,14 +56,23 @@ hipError_t launch_instance(const KernelArgs& a, hipStream_t st) {
 
 // patch-staged convolution: the LDS size depends on the problem (a.cStageBytes per LDS stage
 // plus, unless the filter is 1x1 or 3x3, one raw filter region of BM * R*S*BKC elements).
-template <typename C, int FMODE, bool THROUGH>
-hipError_t launch_conv_route(const KernelArgs& a, hipStream_t st, int raw_bytes) {
+template <typename C, int FMODE, bool THROUGH, bool TAIL>
+hipError_t launch_conv_tail(const KernelArgs& a, hipStream_t st, int raw_bytes) {
   static std::atomic<uint64_t> done{0};
-  hipError_t e = allow_dynamic_lds(conv_patch_kernel<C, FMODE, THROUGH>, 160 * 1024, done);
+  hipError_t e = allow_dynamic_lds(conv_patch_kernel<C, FMODE, THROUGH, TAIL>, 160 * 1024, done);
   if (e != hipSuccess) return e;
   const unsigned grid = (unsigned)a.tiles_m * (unsigned)a.tiles_n;
-  hipLaunchKernelGGL((conv_patch_kernel<C, FMODE, THROUGH>), dim3(grid), dim3(C::THREADS), C::LSTAGES * a.cStageBytes + raw_bytes, st, a);
+  hipLaunchKernelGGL((conv_patch_kernel<C, FMODE, THROUGH, TAIL>), dim3(grid), dim3(C::THREADS), C::LSTAGES * a.cStageBytes + raw_bytes, st, a);
   return hipGetLastError();
+}
+
+// The element-wise fetch of the input tensor's last vector is compiled only into the launches that can need it:
+// 16-bit elements and an odd row length (any other vector that runs past the end starts on a dword boundary and
+// the buffer's range check returns its valid part).
+template <typename C, int FMODE, bool THROUGH>
+hipError_t launch_conv_route(const KernelArgs& a, hipStream_t st, int raw_bytes) {
+  return ((a.cW * C::ES) & 3) != 0 ? launch_conv_tail<C, FMODE, THROUGH, true>(a, st, raw_bytes)
+                                   : launch_conv_tail<C, FMODE, THROUGH, false>(a, st, raw_bytes);
 }
 
 // The output is stored write-through when the reduction is shallow (the stores are then a large share of
