@@ -994,32 +994,43 @@ __global__ __launch_bounds__(C::THREADS) void contraction_kernel(const KernelArg
     // drains one tile's stores under the next tile's loop.  The policy is an immediate of the store
     // instruction; choosing it at run time (two copies of this loop behind a branch) cost every shape 1-2 %.
     constexpr int STORE_POLICY = 16;
+    // One store costs an accumulator read, the scaling, one add and the store: the column part of the offset (or
+    // an out-of-range one: adding a row offset below 2^31 keeps it out of range) is selected once per block column,
+    // the row part is a per-lane base plus a multiple of the row pitch that is the same for the whole wave, and
+    // whether C is read (beta) is decided once per block, not per element.
+    const uint32_t pitch = (uint32_t)args.ldc * OS;
+    auto store_block = [&](int bi, int bj, uint32_t lane_off, auto beta_tag) {
+      constexpr bool with_beta = decltype(beta_tag)::value;
 #pragma unroll
-    for (int bi = 0; bi < C::MBLK; ++bi)
-#pragma unroll
-      for (int bj = 0; bj < C::NBLK; ++bj) {
-        const int col = block_col(bj) + frow;
-        const bool col_ok = col < cols_valid;
-#pragma unroll
-        for (int v = 0; v < MF::NACC; ++v) {
-          const int r = (MB == 32) ? 8 * (v / 4) + 4 * fgrp + (v % 4) : 4 * fgrp + v;
-          const int row = block_row(bi) + r;
-          const uint32_t off = col_ok ? (uint32_t)((row * (int)args.ldc + col) * OS) : OOB;
-          float x = alpha * acc[bi][bj][v];
-          if constexpr (OS == 4) {
-            if (beta != 0.f) x += beta * as_f32(__builtin_amdgcn_raw_buffer_load_b32(rc, off, 0, 0));
-            __builtin_amdgcn_raw_buffer_store_b32(as_u32(x), rc, off, 0, STORE_POLICY);
-          } else {
-            if (beta != 0.f) {
-              const uint16_t old = __builtin_amdgcn_raw_buffer_load_b16(rc, off, 0, 0);
-              x += beta * to_float<OutT>(&old, 0);
-            }
-            uint16_t bits;
-            store_out<OutT>(&bits, 0, x);
-            __builtin_amdgcn_raw_buffer_store_b16(bits, rc, off, 0, STORE_POLICY);
+      for (int v = 0; v < MF::NACC; ++v) {
+        const int r = (MB == 32) ? 8 * (v / 4) + (v % 4) : v;      // row inside the block, less the lane group's 4 * fgrp
+        const uint32_t off = lane_off + (uint32_t)r * pitch;
+        float x = alpha * acc[bi][bj][v];
+        if constexpr (OS == 4) {
+          if constexpr (with_beta) x += beta * as_f32(__builtin_amdgcn_raw_buffer_load_b32(rc, off, 0, 0));
+          __builtin_amdgcn_raw_buffer_store_b32(as_u32(x), rc, off, 0, STORE_POLICY);
+        } else {
+          if constexpr (with_beta) {
+            const uint16_t old = __builtin_amdgcn_raw_buffer_load_b16(rc, off, 0, 0);
+            x += beta * to_float<OutT>(&old, 0);
           }
+          uint16_t bits;
+          store_out<OutT>(&bits, 0, x);
+          __builtin_amdgcn_raw_buffer_store_b16(bits, rc, off, 0, STORE_POLICY);
         }
       }
+    };
+#pragma unroll
+    for (int bj = 0; bj < C::NBLK; ++bj) {
+      const int col = block_col(bj) + frow;
+      const uint32_t col_off = col < cols_valid ? (uint32_t)(col * OS) : OOB;
+#pragma unroll
+      for (int bi = 0; bi < C::MBLK; ++bi) {
+        const uint32_t lane_off = col_off + (uint32_t)(block_row(bi) + 4 * fgrp) * pitch;
+        if (beta != 0.f) store_block(bi, bj, lane_off, std::true_type{});
+        else store_block(bi, bj, lane_off, std::false_type{});
+      }
+    }
   }
 }
 
