@@ -394,7 +394,7 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   double overlap = 0.8 + 0.15 * par;
   if (direct && v.bsrc == B_KC) overlap += 0.05;      // measured: what direct staging pays for k-contiguous operands
   if (direct && v.bsrc == B_NC) overlap += 0.03;      // ... and for an n-contiguous B
-  if (direct && v.bsrc == B_KC && stages == 2 && wm * wn >= 128 * 128 && bk == 4 * kg) overlap += 0.16;   // the two-steps-ahead schedule of the one-wave-per-SIMD tiles (k-contiguous operands: measured)
+  if (direct && v.bsrc == B_KC && stages == 2 && wm * wn >= 128 * 128 && bk == 4 * kg) overlap += 0.24;   // the two-steps-ahead schedule of the one-wave-per-SIMD tiles (k-contiguous operands: measured)
   double t_main = t_mfma;
   if (t_lds > t_main) t_main = t_lds;
   if (t_feed > t_main) t_main = t_feed;
@@ -403,20 +403,33 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
   const double t_ktile = 0.3 * hw.latency_ns[0] * 1e-3;
   auto sync_time = [&](double tiles_k) {
     double t = tiles_k * t_ktile;
-    if (stages > 2 && (v.bsrc == B_KC || v.bsrc == B_NC)) t = t / (stages - 1);
+    // (a ring fills stages - 1 tiles before its first product: those boundaries are paid in full, measured as no gain
+    // from the ring on a 12-tile loop and 7-13 % on 48 to 128 tiles)
+    if (stages > 2 && (v.bsrc == B_KC || v.bsrc == B_NC)) {
+      const double fill = tiles_k < stages - 1.0 ? tiles_k : stages - 1.0;
+      t = t_ktile * (fill + (tiles_k - fill) / (stages - 1));
+    }
     if (stages == 1) t = t + (tiles_k - 1.0) * 4.0 * t_ktile;          // a single buffer: each further tile waits out its own fetch
     return t;
   };
   // (a second resident workgroup works while the first waits at its k tile boundary)
   const double share = resident < 2.0 ? resident : 2.0;
   // (a twentieth of the LDS traffic time is never hidden: fragment reads that conflict cost even where the LDS is not the limit)
-  const double t_part = t_main * (nk_part / nk) / overlap + sync_time(nk_part) / share + 0.05 * t_lds * (nk_part / nk);     // one part of a split tile
-  t_main = t_main / overlap + sync_time(nk) / share + 0.05 * t_lds;
+  // a stride-2 row of a pointwise convolution's input is fetched whole and half of it dropped: the B tile's feed is
+  // paid a second time, unhidden (measured: at equal area the wider pixel tile is 12-14 % slower on such a layer)
+  const double t_s2 = v.bsrc == B_NCS2 ? 2.0 * e * kp * bn / l2_bw : 0.0;
+  // at equal area the taller tile is 1-3 % faster than the wider one on 10 of 13 measured pairs: priced as 1 %
+  const double wide = bn > bm ? 1.01 : 1.0;
+  const double t_part = wide * (t_main * (nk_part / nk) / overlap + sync_time(nk_part) / share + (0.05 * t_lds + t_s2) * (nk_part / nk));     // one part of a split tile
+  t_main = wide * (t_main / overlap + sync_time(nk) / share + 0.05 * t_lds + t_s2);
   const double hbm_bw_cu = hw.bandwidth_gbs[0] * 1e3 / hw.compute_units;
   const double t_epi = bm * bn * eo / (1.2 * hbm_bw_cu);      // write-through stores
   const double t_fill = (hw.latency_ns[0] * 2.0 + hw.latency_ns[1] * 4.0) * 1e-3;
-  // a second resident workgroup hides the stores of the first; further ones add nothing
-  const double hide = resident < 2.0 ? resident : 2.0;
+  // stores are hidden by the other waves on the SIMD, of this workgroup or of another resident one (measured on the
+  // store-bound shapes: eight-wave 128x128 tiles beat four-wave ones by 8 %, four-wave 256x256 tiles trail by 20 %);
+  // beyond four waves per SIMD nothing more is hidden
+  double hide = resident * nwaves / hw.simds_per_cu;
+  if (hide > 4.0) hide = 4.0;
   // a part writes its partial tile, and one part in `split` reads the others' and stores C
   const double t_swap = bm * bn * 4.0 / (0.8 * hbm_bw_cu);
   // the exchange is a chain of memory round trips whatever the tile size: the slot stores written through and awaited,
@@ -427,7 +440,8 @@ double predict(const GemmView& v, const gensor_hw& hw, int bm, int bn, int bk, i
                       cu_part * (t_part + t_chain + t_swap + (t_swap * (split - 1) + t_epi) / split / hide) + t_fill;
   const double bytes_total = (double)v.batch * ((double)e * ((double)v.M * v.K + (double)v.K * v.N) + (double)eo * v.M * v.N);
   const double bytes_swap = split > 1 ? (tiles - whole) * (2.0 * split - 1.0) * bm * bn * 4.0 : 0.0;
-  const double t_hbm = bytes_total / (0.6 * hw.bandwidth_gbs[0] * 1e3) + bytes_swap / (0.25 * hw.bandwidth_gbs[0] * 1e3);
+  // (the store-bound shapes stream at 6.5-6.9 TB/s, measured)
+  const double t_hbm = bytes_total / (0.9 * hw.bandwidth_gbs[0] * 1e3) + bytes_swap / (0.25 * hw.bandwidth_gbs[0] * 1e3);
   // soft roofline: the smaller of the two limits still costs a fraction (imperfect overlap)
   const bool prepass = v.pointwise && v.cstride > 1 && v.bsrc != B_NCS2;   // the input is compacted by a dependent launch of its own
   return (t_cu > t_hbm ? t_cu : t_hbm) + 0.2 * (t_cu > t_hbm ? t_hbm : t_cu) + hw.launch_us * (prepass ? 3.5 : 1.0) +
