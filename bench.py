@@ -17,7 +17,7 @@ Every row but the headline's `value` is timed by one protocol that does not depe
 that settle the shader clock, then the median of 5 event-bracketed batches of at least 50 launches.
 The long sections (per-shape details, unbalanced and deep-k GEMMs, output-type variants, the other
 operators of the paper's table, the walk ablation) go to the file named by --details
-(default gpurun_out/bench_details.json); one progress line per section goes to stderr.
+(see its default below); one progress line per section goes to stderr.
 """
 import argparse
 import json
